@@ -1,0 +1,163 @@
+/*
+ * anchor_attention.h -- C ABI of the MI355X (gfx950) AnchorAttention prefill library.
+ *
+ * The library implements the three stages of AnchorAttention's sparse causal
+ * prefill attention (arXiv 2505.23520, Section 3; Algorithms 1-3) as hand-written
+ * HIP kernels, one GPU, plus a dense causal flash kernel used as comparator.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  * Every data pointer is caller-owned DEVICE memory; `params` is a HOST struct;
+ *    `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *  * The library never allocates, frees or keeps device memory and never
+ *    synchronises the stream: calls only enqueue kernels.  The caller keeps all
+ *    buffers alive until the stream has run them.
+ *  * Return value: 0 on success, a negative AA_E* code otherwise.  All argument
+ *    checks run on the host before anything is enqueued, so a failing call has
+ *    no effect on the device.  anchor_strerror() names a code.
+ *  * Tokens are 0-indexed inside their own sequence.  With b_q = block_q,
+ *    query block i = r / b_q, group g = i / step, G_g = g*step*b_q,
+ *    W_g = max(n_init, G_g - window):
+ *        anchor set   A(r) = { j < n_init, j <= r }  u  { W_g <= j <= r }
+ *        candidates   C_g  = [ n_init, W_g )
+ *    Scores are S(r,j) = softmax_scale * <q_r, k_j> (Eq. 1), theta is in natural
+ *    log units.  Query head h reads KV head h / (Hq/Hkv); every query head runs
+ *    the whole method on its own.
+ *
+ * Layouts
+ * -------
+ *  q, out: element (b, h, r, c) at  b*stride[0] + h*stride[1] + r*stride[2] + c
+ *  k, v  : same with KV heads.  The last dimension (d) is contiguous.  Strides
+ *  are in ELEMENTS.  dtype AA_BF16: 2-byte bfloat16, AA_FP32: 4-byte float.
+ *  Packed variable-length batches (cu_seqlens != NULL): sequence b holds tokens
+ *  cu_seqlens[b] .. cu_seqlens[b+1]-1 of a packed token axis; stride[0] is
+ *  ignored, r is replaced by cu_seqlens[b] + r, N is the longest sequence and
+ *  total_tokens = cu_seqlens[B].
+ *
+ *  Per-row arrays (M, L, lse; Acc has d floats per row), float:
+ *      fixed length: row (b,h,r) at (b*Hq + h)*N + r
+ *      packed      : row (b,h,r) at h*total_tokens + cu_seqlens[b] + r
+ *  Per-block arrays (xa_pooled), float, nblk(b) = ceil(len_b / b_q):
+ *      fixed length: (b*Hq + h)*nblk + i
+ *      packed      : h*blk_cap + (sum_{b'<b} nblk(b')) + i,  blk_cap from anchor_sizes()
+ *  Per-group arrays (counts, offsets), ngrp(b) = ceil(len_b / (b_q*step)):
+ *      fixed length: t = (b*Hq + h)*ngrp + g
+ *      packed      : t = h*grp_cap + (sum_{b'<b} ngrp(b')) + g, grp_cap from anchor_sizes()
+ *  Selected columns: group t owns idx[offsets[t] .. offsets[t] + counts[t]),
+ *  strictly ascending key positions inside the sequence.  offsets[t] is a
+ *  multiple of 64 and the slots up to the next multiple of 64 after the list
+ *  repeat the list's last entry (key n_init when the list is empty), so a reader
+ *  may always fetch whole 64-entry chunks.
+ */
+#ifndef ANCHOR_ATTENTION_H
+#define ANCHOR_ATTENTION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { AA_FP32 = 0, AA_BF16 = 1 };
+
+enum {
+    AA_OK = 0,
+    AA_EINVAL = -1,       /* null pointer, non-positive size, Hq % Hkv != 0, bad stride ... */
+    AA_EUNSUPPORTED = -2, /* a combination the kernels do not implement (see anchor_check)  */
+    AA_EWORKSPACE = -3,   /* workspace smaller than anchor_sizes() reports                  */
+    AA_EHIP = -4          /* a kernel launch failed; hipGetLastError text via anchor_last_hip_error */
+};
+
+typedef struct aa_params {
+    int32_t B, Hq, Hkv;       /* batch (sequences), query heads, KV heads (Hq % Hkv == 0)      */
+    int32_t N;                /* sequence length; longest sequence when cu_seqlens != NULL     */
+    int32_t d;                /* head dimension: bf16 -> 128; fp32 -> multiple of 4, <= 128     */
+    int32_t block_q;          /* b_q : bf16 -> 128; fp32 -> 16..128, multiple of 16             */
+    int32_t block_kv;         /* b_kv: tile size of the paper's listings; must equal block_q    */
+    int32_t n_init;           /* initial tokens always attended (paper: one KV block), >= 0     */
+    int32_t window;           /* window reach before the group start, tokens (paper: b_kv), >= 0*/
+    int32_t step;             /* query blocks sharing one list (paper: 16), 1..128              */
+    float   theta;            /* threshold, nats; +INFINITY selects all, -INFINITY none         */
+    float   softmax_scale;    /* 0 -> 1/sqrt(d)                                                 */
+    int32_t causal;           /* must be 1                                                      */
+    int32_t dtype;            /* AA_FP32 or AA_BF16 (q, k, v, out)                              */
+    int32_t use_anchor;       /* 1; 0 = compare against a zero anchor (Table 4, "without")      */
+    int32_t reserved;
+    int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3]; /* batch, head, token; elements */
+    const int32_t *cu_seqlens;/* device int32[B+1] or NULL                                      */
+    int64_t total_tokens;     /* cu_seqlens[B]; ignored when cu_seqlens == NULL                 */
+} aa_params;
+
+/* Element counts of every buffer a caller has to provide (host-side arithmetic only). */
+typedef struct aa_sizes {
+    int64_t rows;             /* floats in M, L, lse                                            */
+    int64_t acc_elems;        /* floats in Acc (= rows * d)                                     */
+    int64_t blk_cap;          /* per-head stride of per-block arrays                            */
+    int64_t blocks;           /* floats in xa_pooled (= Hq * blk_cap, times B when fixed length)*/
+    int64_t grp_cap;          /* per-head stride of per-group arrays                            */
+    int64_t groups;           /* entries in counts; offsets has groups + 1                      */
+    int64_t idx_capacity_max; /* idx entries that hold any outcome (every candidate selected)   */
+    size_t  select_ws_bytes;  /* workspace of stripe_select                                     */
+    size_t  prefill_ws_bytes; /* workspace of anchor_attention_prefill                          */
+} aa_sizes;
+
+/* Validates params (AA_EINVAL / AA_EUNSUPPORTED) and fills *out.  Host only. */
+int anchor_sizes(const aa_params *params, aa_sizes *out);
+
+/*
+ * Stage 1, pattern-based anchor computation (Sec. 3.1, Eq. 1; Algorithm 1).
+ * For every row r:  M = max_{A(r)} S(r,j),  L = sum_{A(r)} exp(S - M),
+ * Acc = sum_{A(r)} exp(S - M) v_j  (Acc may be NULL: not written), and per query
+ * block the pooled anchor xa_pooled = mean of M over the block's rows (Alg. 2,
+ * avgpool of the anchor).
+ */
+int anchor_compute(const aa_params *params, const void *q, const void *k, const void *v,
+                   float *M, float *L, float *Acc, float *xa_pooled, void *stream);
+
+/*
+ * Stage 2, difference-aware stripe identification (Sec. 3.2 mask; Algorithm 2;
+ * the step rule of Sec. 3.4).  For every group: column j of C_g is selected iff
+ * some block i of the group has  xa_pooled_i - scale*<mean of block i's queries, k_j> <= theta.
+ * Writes counts[groups], offsets[groups+1] (int64, see Layouts), and the lists.
+ * If the lists (with padding) need more than idx_capacity entries, *overflow_flag
+ * is set to 1, nothing is written past the capacity, and offsets stay exact;
+ * otherwise it is set to 0.  ws: select_ws_bytes of scratch.
+ */
+int stripe_select(const aa_params *params, const void *q, const void *k, const float *xa_pooled,
+                  int32_t *counts, int64_t *offsets, int32_t *idx, int64_t idx_capacity,
+                  int32_t *overflow_flag, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Stage 3, fine-grained sparse attention (Sec. 3.3, Eq. 3-5; Algorithm 3).
+ * Continues the online softmax of every row from (M, L, Acc) over the gathered
+ * K/V rows of its group's list, out = acc / l.  If M, L and Acc are all NULL the
+ * anchor region is computed inside the kernel instead of being read.  lse
+ * (nullable) receives log sum_{P(r)} exp S(r,j).
+ */
+int sparse_attn(const aa_params *params, const void *q, const void *k, const void *v,
+                const float *M, const float *L, const float *Acc,
+                const int32_t *counts, const int64_t *offsets, const int32_t *idx,
+                void *out, float *lse, void *stream);
+
+/*
+ * The whole prefill path: stage 1 -> 2 -> 3 on one stream, intermediates in ws
+ * (prefill_ws_bytes).  stats (nullable, device int64[4]) receives
+ * { attended (q,k) pairs, total selected list entries, 0, 0 }.
+ */
+int anchor_attention_prefill(const aa_params *params, const void *q, const void *k, const void *v,
+                             void *out, float *lse, int64_t *stats,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/* Exact causal attention with the same tile engine (comparator; theta=+inf target). */
+int dense_causal_flash(const aa_params *params, const void *q, const void *k, const void *v,
+                       void *out, float *lse, void *stream);
+
+const char *anchor_strerror(int code);
+/* Text of the last HIP error this thread's calls ran into ("" if none). */
+const char *anchor_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ANCHOR_ATTENTION_H */

@@ -167,3 +167,21 @@ def run_head(q, k, v, p: OracleParams, groups=None, want_acc: bool = False, atte
 def dense_params(b_q: int) -> OracleParams:
     """theta=+inf: every candidate is selected, so P(r) = [0, r] (dense causal attention)."""
     return OracleParams(b_q=b_q, n_init=0, w=0, step=1, theta=float("inf"))
+
+
+def attend_group(q, k, v, p: OracleParams, g: int, sel: np.ndarray):
+    """Attention of group ``g``'s rows over A(r) plus the columns marked in ``sel`` (uint8[N])."""
+    lib = _load()
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    k = np.ascontiguousarray(k, dtype=np.float32)
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    N, d = q.shape
+    c = _cfg(N, d, p)
+    span = p.b_q * p.step
+    r0, r1 = g * span, min(N, (g + 1) * span)
+    sel = np.ascontiguousarray(sel, dtype=np.uint8)
+    assert sel.shape == (N,)
+    O = np.empty((r1 - r0, d), np.float64)
+    lse = np.empty(r1 - r0, np.float64)
+    pairs = lib.ao_attend_rows(ctypes.byref(c), _ptr(q), _ptr(k), _ptr(v), r0, r1, _ptr(sel), _ptr(O), _ptr(lse))
+    return dict(rows=(r0, r1), O=O, lse=lse, pairs=int(pairs))

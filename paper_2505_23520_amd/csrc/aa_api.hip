@@ -1,0 +1,394 @@
+// Host side of the C ABI (include/anchor_attention.h): argument checks, buffer
+// arithmetic and kernel launches.  Nothing here allocates device memory or waits
+// for the stream.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/anchor_attention.h"
+#include "aa_common.h"
+#include "aa_engine.h"
+#include "aa_select.h"
+
+namespace aa {
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+int hip_fail(hipError_t e, const char* what) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
+    return AA_EHIP;
+}
+#define AA_HIP(call)                                         \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);    \
+    } while (0)
+#define AA_LAUNCHED(name)                                    \
+    do {                                                     \
+        hipError_t e_ = hipGetLastError();                   \
+        if (e_ != hipSuccess) return hip_fail(e_, name);     \
+    } while (0)
+
+inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Plan {
+    KParams kp;
+    aa_sizes sz;
+    int nwords;
+    // byte offsets inside the workspaces
+    size_t sel_qhi, sel_qlo, sel_bits;                       // stripe_select workspace
+    size_t pf_M, pf_L, pf_Acc, pf_xa, pf_counts, pf_offsets, pf_flag, pf_idx, pf_sel;  // prefill workspace
+};
+
+// candidates of one sequence of `len` tokens, each group's count rounded up to a list chunk
+long long padded_candidates(const aa_params* p, long long len) {
+    const long long span = (long long)p->block_q * p->step;
+    long long tot = 0;
+    for (long long g = 0; g * span < len; ++g) {
+        long long W = g * span - p->window;
+        if (W < p->n_init) W = p->n_init;
+        tot += cdiv(W - p->n_init, kIdxPad) * kIdxPad;
+    }
+    return tot;
+}
+
+int make_plan(const aa_params* p, Plan* pl) {
+    if (!p || !pl) return AA_EINVAL;
+    if (p->B <= 0 || p->Hq <= 0 || p->Hkv <= 0 || p->N <= 0 || p->d <= 0) return AA_EINVAL;
+    if (p->Hq % p->Hkv != 0) return AA_EINVAL;
+    if (p->block_q <= 0 || p->block_kv != p->block_q) return AA_EINVAL;
+    if (p->n_init < 0 || p->window < 0 || p->step < 1) return AA_EINVAL;
+    if (std::isnan(p->theta) || std::isnan(p->softmax_scale) || p->softmax_scale < 0.f) return AA_EINVAL;
+    if (p->dtype != AA_FP32 && p->dtype != AA_BF16) return AA_EINVAL;
+    if (p->cu_seqlens && (p->total_tokens <= 0 || p->N > p->total_tokens)) return AA_EINVAL;
+    if (p->causal != 1) return AA_EUNSUPPORTED;
+    if (p->step > 128) return AA_EUNSUPPORTED;
+    const int vec = p->dtype == AA_BF16 ? 8 : 4;             // elements per 16-byte access
+    if (p->dtype == AA_BF16) {
+        if (p->d != 128 || p->block_q != 128) return AA_EUNSUPPORTED;
+    } else {
+        if (p->d != 32 && p->d != 64 && p->d != 128) return AA_EUNSUPPORTED;
+        if (p->block_q < 16 || p->block_q > 128 || p->block_q % 16) return AA_EUNSUPPORTED;
+    }
+    const int64_t* st[4] = {p->q_stride, p->k_stride, p->v_stride, p->o_stride};
+    for (int t = 0; t < 4; ++t) {
+        if (st[t][2] < p->d || st[t][1] <= 0) return AA_EINVAL;
+        for (int e = 0; e < 3; ++e)
+            if (st[t][e] < 0 || st[t][e] % vec) return AA_EINVAL;
+    }
+
+    KParams& k = pl->kp;
+    memset(&k, 0, sizeof(k));
+    k.B = p->B; k.Hq = p->Hq; k.Hkv = p->Hkv; k.N = p->N; k.d = p->d;
+    k.bq = p->block_q; k.n_init = p->n_init; k.w = p->window; k.step = p->step;
+    k.grp = p->Hq / p->Hkv;
+    k.packed = p->cu_seqlens != nullptr;
+    k.use_anchor = p->use_anchor != 0;
+    k.theta = p->theta;
+    k.sigma = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->d);
+    for (int e = 0; e < 3; ++e) {
+        k.qs[e] = p->q_stride[e]; k.ks[e] = p->k_stride[e];
+        k.vs[e] = p->v_stride[e]; k.os[e] = p->o_stride[e];
+    }
+    k.cu = p->cu_seqlens;
+    k.total = k.packed ? p->total_tokens : (long long)p->B * p->N;
+    const long long span = (long long)p->block_q * p->step;
+    k.nblk_max = (int)cdiv(p->N, p->block_q);
+    k.ngrp_max = (int)cdiv(p->N, span);
+
+    aa_sizes& s = pl->sz;
+    memset(&s, 0, sizeof(s));
+    if (k.packed) {
+        s.rows = (int64_t)p->Hq * p->total_tokens;
+        s.blk_cap = p->total_tokens / p->block_q + p->B;
+        s.grp_cap = p->total_tokens / span + p->B;
+        s.blocks = (int64_t)p->Hq * s.blk_cap;
+        s.groups = (int64_t)p->Hq * s.grp_cap;
+        // lists grow faster than linearly with the length, so the worst split of total_tokens
+        // into sequences of at most N tokens is as many full-length sequences as fit
+        const long long full = p->total_tokens / p->N, rest = p->total_tokens % p->N;
+        s.idx_capacity_max = (int64_t)p->Hq * (full * padded_candidates(p, p->N) + padded_candidates(p, rest) +
+                                               (long long)kIdxPad * s.grp_cap);
+    } else {
+        s.rows = (int64_t)p->B * p->Hq * p->N;
+        s.blk_cap = k.nblk_max;
+        s.grp_cap = k.ngrp_max;
+        s.blocks = (int64_t)p->B * p->Hq * s.blk_cap;
+        s.groups = (int64_t)p->B * p->Hq * s.grp_cap;
+        s.idx_capacity_max = (int64_t)p->B * p->Hq * padded_candidates(p, p->N);
+    }
+    if (s.idx_capacity_max < kIdxPad) s.idx_capacity_max = kIdxPad;
+    s.acc_elems = s.rows * p->d;
+    k.blk_cap = s.blk_cap;
+    k.grp_cap = s.grp_cap;
+    pl->nwords = (int)cdiv(p->N, 32);
+
+    size_t off = 0;
+    if (p->dtype == AA_BF16) {
+        pl->sel_qhi = off; off += align256((size_t)s.blocks * 128 * 2);
+        pl->sel_qlo = off; off += align256((size_t)s.blocks * 128 * 2);
+    } else {
+        pl->sel_qhi = off; off += align256((size_t)s.blocks * p->d * 4);
+        pl->sel_qlo = off;
+    }
+    pl->sel_bits = off; off += align256((size_t)s.groups * pl->nwords * 4);
+    s.select_ws_bytes = off;
+
+    off = 0;
+    pl->pf_M = off; off += align256((size_t)s.rows * 4);
+    pl->pf_L = off; off += align256((size_t)s.rows * 4);
+    pl->pf_Acc = off; off += align256((size_t)s.acc_elems * 4);
+    pl->pf_xa = off; off += align256((size_t)s.blocks * 4);
+    pl->pf_counts = off; off += align256((size_t)s.groups * 4);
+    pl->pf_offsets = off; off += align256((size_t)(s.groups + 1) * 8);
+    pl->pf_flag = off; off += 256;
+    pl->pf_idx = off; off += align256((size_t)s.idx_capacity_max * 4);
+    pl->pf_sel = off; off += s.select_ws_bytes;
+    s.prefill_ws_bytes = off;
+    return AA_OK;
+}
+
+bool misaligned(const void* ptr) { return ((uintptr_t)ptr & 15) != 0; }
+
+int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
+    const KParams& k = pl.kp;
+    const unsigned grid = (unsigned)((long long)k.nblk_max * k.Hq * k.B);
+    if (dtype == AA_BF16) {
+        static bool attr_set = false;
+        const size_t lds = engine_bf16_lds_bytes();
+        if (!attr_set) {
+            AA_HIP(hipFuncSetAttribute((const void*)engine_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds));
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(128), lds, st, ea);
+        AA_LAUNCHED("engine_bf16_kernel");
+    } else {
+        const size_t lds = engine_fp32_lds_bytes(k.d, k.bq);
+        static bool attr_set32 = false;
+        if (!attr_set32) {
+            AA_HIP(hipFuncSetAttribute((const void*)engine_fp32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)engine_fp32_lds_bytes(128, 128)));
+            attr_set32 = true;
+        }
+        hipLaunchKernelGGL(engine_fp32_kernel, dim3(grid), dim3(2 * k.bq), lds, st, ea);
+        AA_LAUNCHED("engine_fp32_kernel");
+    }
+    return AA_OK;
+}
+
+int run_anchor(const Plan& pl, const aa_params* p, const void* q, const void* k, const void* v, float* M, float* L,
+               float* Acc, float* xa, hipStream_t st) {
+    EngineArgs ea;
+    memset(&ea, 0, sizeof(ea));
+    ea.p = pl.kp;
+    ea.flags = kEngAnchorRegion | kEngStoreState;
+    ea.q = q; ea.k = k; ea.v = v;
+    ea.Mout = M; ea.Lout = L; ea.Accout = Acc; ea.xa = xa;
+    return launch_engine(pl, p->dtype, ea, st);
+}
+
+int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k, const float* xa, int32_t* counts,
+               int64_t* offsets, int32_t* idx, int64_t cap, int32_t* flag, char* ws, hipStream_t st) {
+    const KParams& kp = pl.kp;
+    SelectArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    sa.p = kp;
+    sa.q = q; sa.k = k; sa.xa = xa;
+    sa.qp_hi = ws + pl.sel_qhi; sa.qp_lo = ws + pl.sel_qlo; sa.qp_f32 = (float*)(ws + pl.sel_qhi);
+    sa.bits = (unsigned*)(ws + pl.sel_bits);
+    sa.nwords = pl.nwords;
+    sa.keys_per_chunk = 2048;
+    sa.counts = counts; sa.offsets = (long long*)offsets; sa.idx = idx;
+    sa.idx_capacity = cap; sa.overflow = flag;
+    sa.groups_total = pl.sz.groups;
+
+    const dim3 gblk(kp.nblk_max, kp.Hq, kp.B), ggrp(kp.ngrp_max, kp.Hq, kp.B);
+    if (kp.packed) {
+        hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)cdiv(pl.sz.groups, 256)), dim3(256), 0, st, counts,
+                           (long long)pl.sz.groups);
+        AA_LAUNCHED("zero_i32_kernel");
+    }
+    if (p->dtype == AA_BF16) {
+        hipLaunchKernelGGL(pool_q_bf16_kernel, gblk, dim3(128), 0, st, sa);
+        AA_LAUNCHED("pool_q_bf16_kernel");
+        const int RT = 128 - 128 % kp.step;
+        const dim3 gm((unsigned)cdiv(kp.N, sa.keys_per_chunk), (unsigned)cdiv(kp.nblk_max, RT),
+                      (unsigned)(kp.B * kp.Hq));
+        hipLaunchKernelGGL(mask_bf16_kernel, gm, dim3(256), 0, st, sa);
+        AA_LAUNCHED("mask_bf16_kernel");
+    } else {
+        hipLaunchKernelGGL(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);
+        AA_LAUNCHED("pool_q_fp32_kernel");
+        const dim3 gm((unsigned)cdiv(kp.N, 256), (unsigned)kp.ngrp_max, (unsigned)(kp.B * kp.Hq));
+        hipLaunchKernelGGL(mask_fp32_kernel, gm, dim3(256), (size_t)kp.step * kp.d * 4, st, sa);
+        AA_LAUNCHED("mask_fp32_kernel");
+    }
+    hipLaunchKernelGGL(count_kernel, ggrp, dim3(64), 0, st, sa);
+    AA_LAUNCHED("count_kernel");
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, sa);
+    AA_LAUNCHED("scan_kernel");
+    hipLaunchKernelGGL(fill_kernel, ggrp, dim3(256), 0, st, sa);
+    AA_LAUNCHED("fill_kernel");
+    return AA_OK;
+}
+
+int run_sparse(const Plan& pl, const aa_params* p, const void* q, const void* k, const void* v, const float* M,
+               const float* L, const float* Acc, const int32_t* counts, const int64_t* offsets, const int32_t* idx,
+               void* out, float* lse, hipStream_t st) {
+    EngineArgs ea;
+    memset(&ea, 0, sizeof(ea));
+    ea.p = pl.kp;
+    ea.flags = kEngList | kEngStoreOut | (M ? kEngLoadState : kEngAnchorRegion);
+    ea.q = q; ea.k = k; ea.v = v;
+    ea.Min = M; ea.Lin = L; ea.Accin = Acc;
+    ea.counts = counts; ea.offsets = (const long long*)offsets; ea.idx = idx;
+    ea.out = out; ea.lse = lse;
+    return launch_engine(pl, p->dtype, ea, st);
+}
+
+// stats[0] += attended pairs, stats[1] += selected entries.  grid (ngrp_max, Hq, B), 64 threads.
+__global__ __launch_bounds__(64) void stats_kernel(KParams p, const int* counts, unsigned long long* stats) {
+    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const Seq sq = seq_of(p, b);
+    const int span = p.bq * p.step;
+    if ((long long)g * span >= sq.len) return;
+    const int W = window_start(p, g);
+    const int r0 = g * span, r1 = min(r0 + span, sq.len);
+    const int cnt = counts[grp_index(p, sq, b, h, g)];
+    unsigned long long pairs = 0;
+    for (int r = r0 + threadIdx.x; r < r1; r += 64)
+        pairs += (unsigned long long)(min(p.n_init, r + 1) + max(0, r - W + 1) + cnt);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) pairs += __shfl_xor(pairs, off, 64);
+    if (threadIdx.x == 0) {
+        atomicAdd(&stats[0], pairs);
+        atomicAdd(&stats[1], (unsigned long long)cnt);
+    }
+}
+
+__global__ void zero_u64_kernel(unsigned long long* x, int nelem) {
+    if ((int)threadIdx.x < nelem) x[threadIdx.x] = 0ull;
+}
+
+}  // namespace
+}  // namespace aa
+
+using namespace aa;
+
+extern "C" {
+
+int anchor_sizes(const aa_params* params, aa_sizes* out) {
+    Plan pl;
+    int rc = make_plan(params, &pl);
+    if (rc != AA_OK) return rc;
+    if (!out) return AA_EINVAL;
+    *out = pl.sz;
+    return AA_OK;
+}
+
+int anchor_compute(const aa_params* params, const void* q, const void* k, const void* v, float* M, float* L,
+                   float* Acc, float* xa_pooled, void* stream) {
+    Plan pl;
+    int rc = make_plan(params, &pl);
+    if (rc != AA_OK) return rc;
+    if (!q || !k || !v || !M || !L || !xa_pooled) return AA_EINVAL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(Acc)) return AA_EINVAL;
+    return run_anchor(pl, params, q, k, v, M, L, Acc, xa_pooled, (hipStream_t)stream);
+}
+
+int stripe_select(const aa_params* params, const void* q, const void* k, const float* xa_pooled, int32_t* counts,
+                  int64_t* offsets, int32_t* idx, int64_t idx_capacity, int32_t* overflow_flag, void* ws,
+                  size_t ws_bytes, void* stream) {
+    Plan pl;
+    int rc = make_plan(params, &pl);
+    if (rc != AA_OK) return rc;
+    if (!q || !k || !xa_pooled || !counts || !offsets || !idx || !overflow_flag || !ws) return AA_EINVAL;
+    if (idx_capacity < 0 || misaligned(q) || misaligned(k) || misaligned(idx) || misaligned(ws)) return AA_EINVAL;
+    if (ws_bytes < pl.sz.select_ws_bytes) return AA_EWORKSPACE;
+    return run_select(pl, params, q, k, xa_pooled, counts, offsets, idx, idx_capacity, overflow_flag, (char*)ws,
+                      (hipStream_t)stream);
+}
+
+int sparse_attn(const aa_params* params, const void* q, const void* k, const void* v, const float* M, const float* L,
+                const float* Acc, const int32_t* counts, const int64_t* offsets, const int32_t* idx, void* out,
+                float* lse, void* stream) {
+    Plan pl;
+    int rc = make_plan(params, &pl);
+    if (rc != AA_OK) return rc;
+    if (!q || !k || !v || !counts || !offsets || !idx || !out) return AA_EINVAL;
+    const int nstate = (M != nullptr) + (L != nullptr) + (Acc != nullptr);
+    if (nstate != 0 && nstate != 3) return AA_EINVAL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(idx) || misaligned(Acc))
+        return AA_EINVAL;
+    return run_sparse(pl, params, q, k, v, M, L, Acc, counts, offsets, idx, out, lse, (hipStream_t)stream);
+}
+
+int anchor_attention_prefill(const aa_params* params, const void* q, const void* k, const void* v, void* out,
+                             float* lse, int64_t* stats, void* ws, size_t ws_bytes, void* stream) {
+    Plan pl;
+    int rc = make_plan(params, &pl);
+    if (rc != AA_OK) return rc;
+    if (!q || !k || !v || !out || !ws) return AA_EINVAL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(ws)) return AA_EINVAL;
+    if (ws_bytes < pl.sz.prefill_ws_bytes) return AA_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    char* w = (char*)ws;
+    float* M = (float*)(w + pl.pf_M);
+    float* L = (float*)(w + pl.pf_L);
+    float* Acc = (float*)(w + pl.pf_Acc);
+    float* xa = (float*)(w + pl.pf_xa);
+    int32_t* counts = (int32_t*)(w + pl.pf_counts);
+    int64_t* offsets = (int64_t*)(w + pl.pf_offsets);
+    int32_t* flag = (int32_t*)(w + pl.pf_flag);
+    int32_t* idx = (int32_t*)(w + pl.pf_idx);
+    rc = run_anchor(pl, params, q, k, v, M, L, Acc, xa, st);
+    if (rc != AA_OK) return rc;
+    rc = run_select(pl, params, q, k, xa, counts, offsets, idx, pl.sz.idx_capacity_max, flag, w + pl.pf_sel, st);
+    if (rc != AA_OK) return rc;
+    rc = run_sparse(pl, params, q, k, v, M, L, Acc, counts, offsets, idx, out, lse, st);
+    if (rc != AA_OK) return rc;
+    if (stats) {
+        hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)stats, 4);
+        AA_LAUNCHED("zero_u64_kernel");
+        hipLaunchKernelGGL(stats_kernel, dim3(pl.kp.ngrp_max, pl.kp.Hq, pl.kp.B), dim3(64), 0, st, pl.kp, counts,
+                           (unsigned long long*)stats);
+        AA_LAUNCHED("stats_kernel");
+    }
+    return AA_OK;
+}
+
+int dense_causal_flash(const aa_params* params, const void* q, const void* k, const void* v, void* out, float* lse,
+                       void* stream) {
+    Plan pl;
+    int rc = make_plan(params, &pl);
+    if (rc != AA_OK) return rc;
+    if (!q || !k || !v || !out) return AA_EINVAL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out)) return AA_EINVAL;
+    EngineArgs ea;
+    memset(&ea, 0, sizeof(ea));
+    ea.p = pl.kp;
+    ea.flags = kEngAnchorRegion | kEngDense | kEngStoreOut;
+    ea.q = q; ea.k = k; ea.v = v;
+    ea.out = out; ea.lse = lse;
+    return launch_engine(pl, params->dtype, ea, (hipStream_t)stream);
+}
+
+const char* anchor_strerror(int code) {
+    switch (code) {
+        case AA_OK: return "ok";
+        case AA_EINVAL: return "invalid argument";
+        case AA_EUNSUPPORTED: return "unsupported configuration";
+        case AA_EWORKSPACE: return "workspace too small";
+        case AA_EHIP: return "HIP error";
+        default: return "unknown error code";
+    }
+}
+
+const char* anchor_last_hip_error(void) { return g_hip_err; }
+
+}  // extern "C"

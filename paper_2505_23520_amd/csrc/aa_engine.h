@@ -1,0 +1,35 @@
+// Arguments of the online-softmax tile engines (bf16 MFMA and fp32 vector-FMA).
+#pragma once
+#include "aa_common.h"
+
+namespace aa {
+
+enum : int {
+    kEngAnchorRegion = 1,   // walk the tiles of A(r): initial tokens + window .. diagonal
+    kEngDense = 2,          // with kEngAnchorRegion: A(r) := [0, r] (dense causal attention)
+    kEngList = 4,           // walk the chunks of the group's selected-column list
+    kEngLoadState = 8,      // start from (M, L, Acc) instead of (-inf, 0, 0)
+    kEngStoreState = 16,    // write M, L, (Acc), pooled anchor
+    kEngStoreOut = 32       // write out = acc / l and lse
+};
+
+struct EngineArgs {
+    KParams p;
+    int flags;
+    const void *q, *k, *v;
+    const float *Min, *Lin, *Accin;
+    const int* counts;
+    const long long* offsets;
+    const int* idx;
+    float *Mout, *Lout, *Accout, *xa;
+    void* out;
+    float* lse;
+};
+
+__global__ void engine_bf16_kernel(EngineArgs a);
+size_t engine_bf16_lds_bytes();
+
+__global__ void engine_fp32_kernel(EngineArgs a);
+size_t engine_fp32_lds_bytes(int d, int bq);
+
+}  // namespace aa

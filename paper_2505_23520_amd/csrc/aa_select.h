@@ -1,0 +1,33 @@
+// Arguments of the stage-2 (stripe identification) kernels.
+#pragma once
+#include "aa_common.h"
+
+namespace aa {
+
+struct SelectArgs {
+    KParams p;
+    const void *q, *k;
+    const float* xa;          // pooled anchors, per block
+    void *qp_hi, *qp_lo;      // bf16 path: pooled queries, hi / lo parts, rows of 128
+    float* qp_f32;            // fp32 path: pooled queries, rows of d
+    unsigned* bits;           // [groups][nwords] selection bit words, bit (j % 32) of word j / 32
+    int nwords;               // ceil(N / 32)
+    int keys_per_chunk;       // bf16 mask kernel: keys handled by one work-group (multiple of 128)
+    int* counts;
+    long long* offsets;
+    int* idx;
+    long long idx_capacity;
+    int* overflow;
+    long long groups_total;
+};
+
+__global__ void pool_q_bf16_kernel(SelectArgs a);
+__global__ void pool_q_fp32_kernel(SelectArgs a);
+__global__ void mask_bf16_kernel(SelectArgs a);
+__global__ void mask_fp32_kernel(SelectArgs a);
+__global__ void zero_i32_kernel(int* x, long long nelem);
+__global__ void count_kernel(SelectArgs a);
+__global__ void scan_kernel(SelectArgs a);
+__global__ void fill_kernel(SelectArgs a);
+
+}  // namespace aa

@@ -1,0 +1,336 @@
+// Stage 2 of AnchorAttention, difference-aware stripe identification
+// (arXiv 2505.23520 Sec. 3.2 mask, Algorithm 2, and the step rule of Sec. 3.4):
+//   pool_q   : qbar_i = mean of query block i's rows               (Alg. 2, avgpool(Q))
+//   mask     : bit (g, j) = OR_{i in g} [ xbar_i - sigma <qbar_i, k_j> <= theta ],  j in C_g
+//   count    : |I_g| = popcount of the group's bits
+//   scan     : offsets = exclusive prefix sum of the counts rounded up to 64
+//   fill     : ballot / prefix-popcount stream compaction of the bits into ascending lists
+// The bf16 mask kernel is a skinny MFMA GEMM (pooled rows x keys); the pooled
+// query, an fp32 mean, is split into bf16 hi + lo parts so that the products with
+// the (exactly bf16) keys carry ~16 mantissa bits and the threshold decision does
+// not depend on bf16 rounding of the mean.
+#include "aa_common.h"
+#include "aa_select.h"
+
+namespace aa {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+namespace {
+__device__ __forceinline__ float bf16_to_f(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
+__device__ __forceinline__ unsigned short f_to_bf16_rne(float f) {
+    unsigned u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+}  // namespace
+
+// ------------------------------------------------------------------ pool_q
+// grid (nblk_max, Hq, B), 128 threads.  bf16: writes hi/lo bf16 rows of 128; fp32: float rows of d.
+__global__ __launch_bounds__(128) void pool_q_bf16_kernel(SelectArgs a) {
+    const KParams& p = a.p;
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const Seq sq = seq_of(p, b);
+    const int r0 = i * p.bq;
+    if (r0 >= sq.len) return;
+    const int r1 = min(r0 + p.bq, sq.len);
+    const int tid = threadIdx.x, dp = tid & 63, par = tid >> 6;
+    const unsigned* src = (const unsigned*)((const unsigned short*)a.q + tok_offset(p, p.qs, sq, b, h, 0));
+    const long long st = p.qs[2] / 2;  // dwords per token
+    float s0 = 0.f, s1 = 0.f;
+    for (int r = r0 + par; r < r1; r += 2) {
+        const unsigned x = src[(long long)r * st + dp];
+        s0 += __uint_as_float(x << 16);
+        s1 += __uint_as_float(x & 0xffff0000u);
+    }
+    __shared__ float red[2][64];
+    if (par) { red[0][dp] = s0; red[1][dp] = s1; }
+    __syncthreads();
+    if (!par) {
+        const float inv = 1.f / (float)(r1 - r0);
+        s0 = (s0 + red[0][dp]) * inv;
+        s1 = (s1 + red[1][dp]) * inv;
+        const unsigned short h0 = f_to_bf16_rne(s0), h1 = f_to_bf16_rne(s1);
+        const unsigned short l0 = f_to_bf16_rne(s0 - bf16_to_f(h0)), l1 = f_to_bf16_rne(s1 - bf16_to_f(h1));
+        const long long bi = blk_index(p, sq, b, h, i);
+        ((unsigned*)a.qp_hi)[bi * 64 + dp] = (unsigned)h0 | ((unsigned)h1 << 16);
+        ((unsigned*)a.qp_lo)[bi * 64 + dp] = (unsigned)l0 | ((unsigned)l1 << 16);
+    }
+}
+
+__global__ __launch_bounds__(128) void pool_q_fp32_kernel(SelectArgs a) {
+    const KParams& p = a.p;
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const Seq sq = seq_of(p, b);
+    const int r0 = i * p.bq;
+    if (r0 >= sq.len) return;
+    const int r1 = min(r0 + p.bq, sq.len);
+    const float* src = (const float*)a.q + tok_offset(p, p.qs, sq, b, h, 0);
+    const long long bi = blk_index(p, sq, b, h, i);
+    for (int c = threadIdx.x; c < p.d; c += blockDim.x) {
+        float s = 0.f;
+        for (int r = r0; r < r1; ++r) s += src[(long long)r * p.qs[2] + c];
+        a.qp_f32[bi * p.d + c] = s / (float)(r1 - r0);
+    }
+}
+
+// ------------------------------------------------------------------ mask, bf16 MFMA
+// grid (key chunks, row tiles, B*Hq), 256 threads = 4 waves: wave (wr, wc) owns pooled rows
+// 64 wr .. +64 of the row tile and keys 64 wc .. +64 of every 128-key tile of the chunk.
+// A row tile holds RT = 128 - 128 % step pooled rows, so no group straddles two tiles.
+constexpr int kMaskTileKeys = 128;
+
+__global__ __launch_bounds__(256) void mask_bf16_kernel(SelectArgs a) {
+    const KParams& p = a.p;
+    const int b = blockIdx.z / p.Hq, h = blockIdx.z % p.Hq, hk = h / p.grp;
+    const Seq sq = seq_of(p, b);
+    const int nblk = (sq.len + p.bq - 1) / p.bq;
+    const int RT = 128 - 128 % p.step;
+    const int row_t0 = blockIdx.y * RT;                  // first pooled row (query block) of the tile
+    if (row_t0 >= nblk) return;
+    const int rows_here = min(RT, nblk - row_t0);
+    const int g_first = row_t0 / p.step;
+    const int g_last = (row_t0 + rows_here - 1) / p.step;
+    const int Wmax = window_start(p, g_last);            // candidates of the tile end before Wmax
+    const int key_lo = (p.n_init / kMaskTileKeys) * kMaskTileKeys;
+    const int chunk0 = key_lo + blockIdx.x * a.keys_per_chunk;
+    if (chunk0 >= Wmax) return;
+    const int chunk1 = min(chunk0 + a.keys_per_chunk, ((Wmax + kMaskTileKeys - 1) / kMaskTileKeys) * kMaskTileKeys);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave & 1, wc = wave >> 1;
+    const int n = lane & 31, hf = lane >> 5;
+
+    // B operand: pooled query rows (hi and lo parts); lane (n, hf) holds row n, columns 16 ks + 8 hf .. +8
+    bf16x8 bhi[2][8], blo[2][8];
+    float xb[2];                                          // pooled anchor of the lane's row; NaN = no such row
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int lr = 64 * wr + 32 * rb + n;             // row inside the tile
+        const bool ok = lr < rows_here;
+        const long long bi = blk_index(p, sq, b, h, row_t0 + (ok ? lr : 0));
+        const unsigned short* hi = (const unsigned short*)a.qp_hi + bi * 128;
+        const unsigned short* lo = (const unsigned short*)a.qp_lo + bi * 128;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            uint4 x = *(const uint4*)(hi + 16 * ks + 8 * hf);
+            uint4 y = *(const uint4*)(lo + 16 * ks + 8 * hf);
+            if (!ok) { x = make_uint4(0, 0, 0, 0); y = x; }
+            bhi[rb][ks] = *(bf16x8*)&x;
+            blo[rb][ks] = *(bf16x8*)&y;
+        }
+        xb[rb] = ok ? (p.use_anchor ? a.xa[bi] : 0.f) : __builtin_nanf("");
+    }
+
+    const unsigned short* kbase = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, b, hk, 0);
+    const long long kst = p.ks[2];
+    __shared__ unsigned rowword[128][4];
+    const int nwords = a.nwords;
+    const int ngrp = (nblk + p.step - 1) / p.step;
+
+    for (int t0 = chunk0; t0 < chunk1; t0 += kMaskTileKeys) {
+        // C[key][row]: keys are the M dimension (A operand straight from global memory),
+        // pooled rows the N dimension, so one lane owns one pooled row
+        floatx16 c[2][2];                                 // [kb][rb]
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) c[kb][rb][v] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const int key = min(t0 + 64 * wc + 32 * kb + n, sq.len - 1);
+            const unsigned short* kr = kbase + (long long)key * kst + 8 * hf;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const uint4 x = *(const uint4*)(kr + 16 * ks);
+                const bf16x8 kf = *(const bf16x8*)&x;
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    c[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, blo[rb][ks], c[kb][rb], 0, 0, 0);
+                    c[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, bhi[rb][ks], c[kb][rb], 0, 0, 0);
+                }
+            }
+        }
+        // threshold compare; the lane gathers the bits of its 16 keys per 32-key block, the
+        // other half of the wave holds the remaining 16
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                unsigned wd = 0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const bool pred = (xb[rb] - p.sigma * c[kb][rb][v]) <= p.theta;
+                    wd |= pred ? (1u << (8 * (v >> 2) + (v & 3))) : 0u;
+                }
+                wd <<= 4 * hf;
+                wd |= (unsigned)__shfl_xor((int)wd, 32, 64);
+                if (hf == 0) rowword[64 * wr + 32 * rb + n][2 * wc + kb] = wd;
+            }
+        __syncthreads();
+        // OR the rows of each group, clip to the group's candidate range, write the bit words
+        const int ngt = g_last - g_first + 1;
+        for (int e = tid; e < ngt * 4; e += 256) {
+            const int gi = e >> 2, wi = e & 3;
+            const int g = g_first + gi;
+            const int lr0 = g * p.step - row_t0;
+            unsigned wd = 0;
+            for (int s = 0; s < p.step && lr0 + s < rows_here; ++s) wd |= rowword[lr0 + s][wi];
+            const int j0 = t0 + 32 * wi;
+            const int Wg = window_start(p, g);
+            // keep bits with n_init <= j0 + bit < Wg
+            const int lo = max(p.n_init - j0, 0), hi = min(Wg - j0, 32);
+            unsigned keep = 0;
+            if (hi > lo) keep = (hi - lo >= 32) ? 0xffffffffu : (((1u << (hi - lo)) - 1u) << lo);
+            if (g < ngrp && j0 / 32 < nwords)
+                a.bits[grp_index(p, sq, b, h, g) * nwords + j0 / 32] = wd & keep;
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------ mask, fp32 vector FMA
+// grid (key chunks of 256, ngrp_max, B*Hq), 256 threads: one key per thread.
+__global__ __launch_bounds__(256) void mask_fp32_kernel(SelectArgs a) {
+    const KParams& p = a.p;
+    const int b = blockIdx.z / p.Hq, h = blockIdx.z % p.Hq, hk = h / p.grp;
+    const int g = blockIdx.y;
+    const Seq sq = seq_of(p, b);
+    const int nblk = (sq.len + p.bq - 1) / p.bq;
+    const int i0 = g * p.step;
+    if (i0 >= nblk) return;
+    const int nb = min(p.step, nblk - i0);
+    const int Wg = window_start(p, g);
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if ((int)(blockIdx.x * 256) >= Wg) return;
+    extern __shared__ float qs[];                      // nb pooled rows of d floats
+    for (int e = threadIdx.x; e < nb * p.d; e += 256)
+        qs[e] = a.qp_f32[blk_index(p, sq, b, h, i0 + e / p.d) * p.d + e % p.d];
+    __syncthreads();
+    bool pred = false;
+    if (j >= p.n_init && j < Wg) {
+        const float* kr = (const float*)a.k + tok_offset(p, p.ks, sq, b, hk, j);
+        for (int s = 0; s < nb; ++s) {
+            float dot = 0.f;
+            for (int c = 0; c < p.d; ++c) dot = fmaf(qs[s * p.d + c], kr[c], dot);
+            const float xbar = p.use_anchor ? a.xa[blk_index(p, sq, b, h, i0 + s)] : 0.f;
+            pred = pred || ((xbar - p.sigma * dot) <= p.theta);
+        }
+    }
+    const unsigned long long bal = __ballot(pred);
+    const int lane = threadIdx.x & 63;
+    const long long t = grp_index(p, sq, b, h, g);
+    const int w0 = (blockIdx.x * 256 + (threadIdx.x & ~63)) / 32;
+    if (lane == 0 && w0 < a.nwords) a.bits[t * a.nwords + w0] = (unsigned)bal;
+    if (lane == 32 && w0 + 1 < a.nwords) a.bits[t * a.nwords + w0 + 1] = (unsigned)(bal >> 32);
+}
+
+// ------------------------------------------------------------------ count / scan / fill
+__global__ void zero_i32_kernel(int* x, long long nelem) {
+    long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nelem) x[i] = 0;
+}
+
+// grid (ngrp_max, Hq, B), 64 threads
+__global__ __launch_bounds__(64) void count_kernel(SelectArgs a) {
+    const KParams& p = a.p;
+    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const Seq sq = seq_of(p, b);
+    const int ngrp = (sq.len + p.bq * p.step - 1) / (p.bq * p.step);
+    if (g >= ngrp) return;
+    const int Wg = window_start(p, g);
+    const long long t = grp_index(p, sq, b, h, g);
+    const unsigned* bits = a.bits + t * a.nwords;
+    int c = 0;
+    if (Wg > p.n_init)
+        for (int w = p.n_init / 32 + threadIdx.x; w < (Wg + 31) / 32; w += 64) c += __popc(bits[w]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);
+    if (threadIdx.x == 0) a.counts[t] = c;
+}
+
+// one work-group of 1024 threads: offsets[t] = sum_{t' < t} roundup64(counts[t'])
+__global__ __launch_bounds__(1024) void scan_kernel(SelectArgs a) {
+    const long long T = a.groups_total;
+    const int tid = threadIdx.x;
+    const long long per = (T + 1023) / 1024;
+    const long long lo = min(T, per * tid), hi = min(T, lo + per);
+    long long s = 0;
+    for (long long t = lo; t < hi; ++t) s += (a.counts[t] + kIdxPad - 1) / kIdxPad * (long long)kIdxPad;
+    __shared__ long long part[1024];
+    part[tid] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        long long x = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += x;
+        __syncthreads();
+    }
+    long long run = part[tid] - s;
+    for (long long t = lo; t < hi; ++t) {
+        a.offsets[t] = run;
+        run += (a.counts[t] + kIdxPad - 1) / kIdxPad * (long long)kIdxPad;
+    }
+    if (tid == 1023) {
+        a.offsets[T] = part[1023];
+        if (a.overflow) *a.overflow = part[1023] > a.idx_capacity ? 1 : 0;
+    }
+}
+
+// grid (ngrp_max, Hq, B), 256 threads: expand the group's bit words into its ascending list
+__global__ __launch_bounds__(256) void fill_kernel(SelectArgs a) {
+    const KParams& p = a.p;
+    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const Seq sq = seq_of(p, b);
+    const int ngrp = (sq.len + p.bq * p.step - 1) / (p.bq * p.step);
+    if (g >= ngrp) return;
+    const int Wg = window_start(p, g);
+    if (Wg <= p.n_init) return;
+    const long long t = grp_index(p, sq, b, h, g);
+    const int cnt = a.counts[t];
+    if (cnt == 0) return;
+    const long long base = a.offsets[t];
+    const unsigned* bits = a.bits + t * a.nwords;
+    const int w_lo = p.n_init / 32, w_hi = (Wg + 31) / 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // each wave takes a contiguous quarter of the words
+    const int per = (w_hi - w_lo + 3) / 4;
+    const int a0 = min(w_hi, w_lo + wave * per), a1 = min(w_hi, a0 + per);
+    int c = 0;
+    for (int w = a0 + lane; w < a1; w += 64) c += __popc(bits[w]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);
+    __shared__ int wsum[4];
+    __shared__ int last_key;
+    if (lane == 0) wsum[wave] = c;
+    __syncthreads();
+    long long pos = base;
+    for (int i = 0; i < wave; ++i) pos += wsum[i];
+    // two words per step: lanes 0..31 test word w, lanes 32..63 word w+1
+    for (int w = a0; w < a1; w += 2) {
+        const int wi = w + (lane >> 5);
+        const unsigned wd = wi < a1 ? bits[wi] : 0u;
+        const unsigned first = __shfl(wd, 0, 64);      // word w as seen by every lane
+        const int bit = lane & 31;
+        const bool on = (wd >> bit) & 1u;
+        const int before = __popc(wd & ((1u << bit) - 1u)) + ((lane >> 5) ? __popc(first) : 0);
+        const long long dst = pos + before;
+        if (on && dst < a.idx_capacity) a.idx[dst] = wi * 32 + bit;
+        pos += __popc(first) + __popc(__shfl(wd, 32, 64));
+    }
+    // padding up to the next multiple of 64 repeats the last entry
+    if (tid == 0) {
+        int w = w_hi - 1;
+        while (w > w_lo && bits[w] == 0u) --w;
+        last_key = w * 32 + 31 - __clz(bits[w]);
+    }
+    __syncthreads();
+    const int padded = (cnt + kIdxPad - 1) / kIdxPad * kIdxPad;
+    for (int e = cnt + tid; e < padded; e += 256)
+        if (base + e < a.idx_capacity) a.idx[base + e] = last_key;
+}
+
+}  // namespace aa
