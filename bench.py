@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the AnchorAttention prefill path on one MI355X.
+
+A step is one pass of the whole hot path (anchor computation -> stripe
+identification -> gathered sparse attention) over one attention layer of the
+128k-token GQA workload (32 query / 8 KV heads, d = 128, bf16), inputs already
+resident in HBM.  One JSON line is printed:
+
+  value / ms_per_step : ms per layer of the fused entry point
+  effective_tflops    : 4 * d * attended (q,k) pairs / time
+  stage_ms            : per-stage times (the same kernels through the stage-wise entry
+                        points, HIP events between the launches, same stream)
+  roofline            : stage-3 kernel (the dominant one) against the bf16 MFMA peak
+  dense_flash_ms      : the from-scratch dense causal flash kernel on the same GPU
+  recall              : mean exp(lse_sparse - lse_dense), attention mass kept
+  calibrated          : the same measurements with the planted magnitudes in scaled-logit
+                        units (signal="logit"), the regime where the threshold separates
+                        stripes from background
+  cpu_baseline        : the fp64 CPU oracle timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
+HBM_PEAK = 8.0e12         # B/s
+
+
+def measure(api, torch, synth, wl, signal, step, steps, warmup, theta=None, dense_steps=2, log=None):
+    cfg = api.Config(block=wl.block, n_init=wl.n_init, window=wl.window, step=step,
+                     theta=wl.theta if theta is None else theta)
+    t0 = time.time()
+    seq = synth.make_sequence(wl, 0, signal=signal)
+    q = torch.from_numpy(seq["q"]).to(torch.bfloat16)[None].cuda()
+    k = torch.from_numpy(seq["k"]).to(torch.bfloat16)[None].cuda()
+    v = torch.from_numpy(seq["v"]).to(torch.bfloat16)[None].cuda()
+    del seq
+    if log:
+        log("inputs %s/%s ready in %.1fs" % (wl.name, signal, time.time() - t0))
+    out = torch.empty_like(q)
+    p = api.make_params(cfg, q, k, v, out)
+    sz = api.anchor_sizes(p)
+    ws = torch.empty(sz.prefill_ws_bytes, dtype=torch.uint8, device="cuda")
+    lse = torch.empty(sz.rows, dtype=torch.float32, device="cuda")
+    stats = torch.zeros(4, dtype=torch.int64, device="cuda")
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    # ---- fused entry point: the timed step
+    for _ in range(warmup):
+        api.anchor_attention_prefill(p, q, k, v, out, lse, stats, ws)
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(steps):
+        api.anchor_attention_prefill(p, q, k, v, out, lse, stats, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    pairs, selected = int(stats[0]), int(stats[1])
+    if log:
+        log("fused: %.3f ms/layer, pairs %.4g" % (ms, pairs))
+
+    # ---- per-stage times: same kernels through the stage-wise entry points
+    B = api.alloc_stage_buffers(p)
+    marks = [[ev() for _ in range(4)] for _ in range(steps)]
+    api.anchor_compute(p, q, k, v, B["M"], B["L"], B["Acc"], B["xa"])
+    api.stripe_select(p, q, k, B["xa"], B["counts"], B["offsets"], B["idx"], B["flag"], B["ws"])
+    api.sparse_attn(p, q, k, v, B["M"], B["L"], B["Acc"], B["counts"], B["offsets"], B["idx"], out, B["lse"])
+    torch.cuda.synchronize()
+    for m in marks:
+        m[0].record()
+        api.anchor_compute(p, q, k, v, B["M"], B["L"], B["Acc"], B["xa"])
+        m[1].record()
+        api.stripe_select(p, q, k, B["xa"], B["counts"], B["offsets"], B["idx"], B["flag"], B["ws"])
+        m[2].record()
+        api.sparse_attn(p, q, k, v, B["M"], B["L"], B["Acc"], B["counts"], B["offsets"], B["idx"], out, B["lse"])
+        m[3].record()
+    torch.cuda.synchronize()
+    stage = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / steps for i in range(3)]
+    assert int(B["flag"]) == 0
+    list_pairs = int((B["counts"].to(torch.int64).view(-1, sz.grp_cap) *
+                      torch.tensor([min(wl.block * step, wl.seqlens[0] - g * wl.block * step)
+                                    for g in range(sz.grp_cap)], device="cuda")).sum())
+    sparse_lse = B["lse"].clone()
+    del B
+
+    # ---- dense causal flash on the same GPU
+    dlse = torch.empty(sz.rows, dtype=torch.float32, device="cuda")
+    dout = torch.empty_like(q)
+    api.dense_causal_flash(p, q, k, v, dout, dlse)
+    torch.cuda.synchronize()
+    d0, d1 = ev(), ev()
+    d0.record()
+    for _ in range(dense_steps):
+        api.dense_causal_flash(p, q, k, v, dout, dlse)
+    d1.record()
+    torch.cuda.synchronize()
+    dense_ms = d0.elapsed_time(d1) / dense_steps
+    recall = float(torch.exp(sparse_lse - dlse).double().mean())
+    N, Hq, d = wl.seqlens[0], wl.Hq, wl.d
+    causal_pairs = Hq * N * (N + 1) // 2
+    res = dict(
+        ms_per_layer=ms, attended_pairs=pairs, selected_entries=selected,
+        sparsity=1.0 - pairs / causal_pairs,
+        effective_tflops=4.0 * d * pairs / (ms * 1e-3) / 1e12,
+        stage_ms=dict(anchor=stage[0], select=stage[1], sparse=stage[2]),
+        stage3_list_pairs=list_pairs,
+        stage3_tflops=4.0 * d * list_pairs / (stage[2] * 1e-3) / 1e12 if list_pairs else 0.0,
+        dense_flash_ms=dense_ms, dense_flash_tflops=4.0 * d * causal_pairs / (dense_ms * 1e-3) / 1e12,
+        speedup_vs_dense=dense_ms / ms, recall=recall, theta=cfg.theta, step=step, signal=signal,
+    )
+    if log:
+        log(json.dumps(res))
+    return res, (q, k, v)
+
+
+def cpu_baseline(synth, wl, step, signal, budget_s=20.0):
+    """Oracle (as it stands) on host cores, on one (head, group) unit of the same workload."""
+    from oracle import anchor_oracle as ao
+    N = wl.seqlens[0]
+    span = wl.block * step
+    seq = synth.make_sequence(wl, 0, signal=signal, heads_kv=[0])
+    op = ao.OracleParams(b_q=wl.block, n_init=wl.n_init, w=wl.window, step=step, theta=wl.theta)
+    # a group whose cost is roughly budget_s of CPU work: rows*keys pairs at ~2e7 pairs/s/core
+    cores = os.cpu_count() or 1
+    omp = int(os.environ.get("OMP_NUM_THREADS", cores))
+    cores = min(cores, omp)
+    target_pairs = budget_s * 1.0e7 * cores
+    g = int(min(N // span - 1, max(1, target_pairs / span / span)))
+    t0 = time.time()
+    r = ao.run_group(seq["q"][0], seq["k"][0], seq["v"][0], op, g)
+    dt = time.time() - t0
+    return dict(seconds=dt, pairs=r["pairs"], group=g, cores=cores, selected=int(r["idx"].size))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="gqa_128k")
+    ap.add_argument("--step", type=int, default=16, help="query blocks sharing one list (paper default 16)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-calibrated", action="store_true")
+    ap.add_argument("--signal", default="literal", choices=["literal", "logit"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU only (the path shards by heads with no exchange step; "
+                 "this build has no multi-GPU code): run with --gpus 1")
+
+    import torch
+    from paper_2505_23520_amd import api, synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = synth.workloads()[args.workload]
+    log = lambda s: print("[bench] " + s, file=sys.stderr, flush=True)
+
+    main_res, tensors = measure(api, torch, synth, wl, args.signal, args.step, args.steps, args.warmup, log=log)
+    del tensors
+    torch.cuda.empty_cache()
+    calibrated = None
+    if not args.no_calibrated and args.signal == "literal":
+        calibrated, t2 = measure(api, torch, synth, wl, "logit", args.step, args.steps, args.warmup, log=log)
+        del t2
+        torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.no_cpu:
+        c = cpu_baseline(synth, wl, args.step, args.signal)
+        layer_ms = c["seconds"] * 1e3 * main_res["attended_pairs"] / max(1, c["pairs"])
+        cpu = dict(value=layer_ms, unit="ms/layer (sample time scaled by attended pairs)", cores=c["cores"],
+                   kind="oracle",
+                   sample="query head 0, group %d (%d rows) of %s: %.1f s for %.3g pairs" % (
+                       c["group"], wl.block * args.step, wl.name, c["seconds"], c["pairs"]))
+        log(json.dumps(cpu))
+
+    N, d = wl.seqlens[0], wl.d
+    s3 = main_res["stage_ms"]["sparse"] * 1e-3
+    flops3 = 4.0 * d * main_res["stage3_list_pairs"]
+    line = {
+        "metric": "prefill attention ms/layer at 128k GQA32/8 d128 bf16 (effective TFLOPS over attended pairs, recall alongside)",
+        "value": main_res["ms_per_layer"], "unit": "ms/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": main_res["ms_per_layer"], "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s (B=1, Hq=%d, Hkv=%d, N=%d, d=%d, block %d, n_init %d, window %d, step %d, theta %.4f, signal %s)" % (
+            wl.name, wl.Hq, wl.Hkv, N, d, wl.block, wl.n_init, wl.window, args.step, wl.theta, args.signal)},
+        "effective_tflops": main_res["effective_tflops"], "sparsity": main_res["sparsity"],
+        "recall": main_res["recall"], "stage_ms": main_res["stage_ms"],
+        "dense_flash_ms": main_res["dense_flash_ms"], "dense_flash_tflops": main_res["dense_flash_tflops"],
+        "speedup_vs_dense": main_res["speedup_vs_dense"],
+        "mfma_peak_frac_whole_path": main_res["effective_tflops"] * 1e12 / MFMA_BF16_PEAK,
+        "roofline": {"kernel": "engine_bf16_kernel (stage 3, gathered sparse attention)", "bound": "mfma",
+                     "achieved": flops3 / s3 / 1e12 if flops3 else 0.0, "peak": MFMA_BF16_PEAK / 1e12,
+                     "unit": "TFLOP/s", "frac": flops3 / s3 / MFMA_BF16_PEAK if flops3 else 0.0, "traffic": None},
+        "calibrated": calibrated,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -69,7 +69,7 @@ def test_fp32_tiny_config(api):
     assert 0 < worst["selected"] <= worst["candidates"]
 
 
-@pytest.mark.parametrize("step,theta", [(1, 1.5), (2, 2.5), (4, 0.5)])
+@pytest.mark.parametrize("step,theta", [(1, 3.5), (2, 5.0), (4, 4.0)])
 def test_fp32_logit_signal_steps(api, step, theta):
     wl = _wl("t", "fp32", [1024], 2, 1, 64, 64, 21, 24)
     cfg = api.Config(block=64, n_init=16, window=64, step=step, theta=theta)
@@ -79,21 +79,21 @@ def test_fp32_logit_signal_steps(api, step, theta):
 
 def test_fp32_ragged_and_other_shapes(api):
     wl = _wl("t", "fp32", [777], 2, 2, 32, 48, 22, 16)
-    cfg = api.Config(block=48, n_init=10, window=30, step=3, theta=2.0)
+    cfg = api.Config(block=48, n_init=10, window=30, step=3, theta=5.0)
     _run_and_check(api, wl, cfg)
     wl = _wl("t", "fp32", [200], 1, 1, 128, 128, 23, 8)
-    cfg = api.Config(block=128, n_init=0, window=0, step=1, theta=3.0)
+    cfg = api.Config(block=128, n_init=0, window=0, step=1, theta=5.0)
     _run_and_check(api, wl, cfg)
 
 
 # ------------------------------------------------------------------ bf16 MFMA path
 @pytest.mark.parametrize("N,step,n_init,window,theta", [
-    (2048, 1, 128, 128, 2.0),
-    (2048, 2, 128, 128, 2.5),
-    (4096, 16, 128, 128, 2.5),
-    (1000, 1, 128, 128, 2.0),        # ragged last block
-    (1500, 4, 64, 192, 1.0),         # ragged, sub-block sink, wider window
-    (1280, 3, 0, 0, 2.0),            # no sink, no extra window, step not a power of two
+    (2048, 1, 128, 128, 3.5),
+    (2048, 2, 128, 128, 5.0),        # threshold in the bulk of the background: many near-threshold columns
+    (4096, 16, 128, 128, 4.0),
+    (1000, 1, 128, 128, 3.5),        # ragged last block
+    (1500, 4, 64, 192, 5.0),         # ragged, sub-block sink, wider window
+    (1280, 3, 0, 0, 4.0),            # no sink, no extra window, step not a power of two
     (640, 5, 200, 100, 3.0),
 ])
 def test_bf16_pipeline(api, N, step, n_init, window, theta):
@@ -145,7 +145,7 @@ def test_bf16_recompute_anchor_in_stage3(api):
     """sparse_attn with M = L = Acc = NULL computes the anchor region itself."""
     from parity_util import GpuRun
     wl = _wl("t", "bf16", [2048], 4, 2, 128, 128, 70, 32)
-    cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=2.0)
+    cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=4.5)
     seqs = [synth.make_sequence(wl, 0, signal="logit")]
     run = GpuRun(api, seqs, cfg, "bf16").stages()
     out2 = torch.zeros_like(run.out)
@@ -160,7 +160,7 @@ def test_bf16_recompute_anchor_in_stage3(api):
 def test_packed_varlen(api):
     for dtype, d, block, lens in (("bf16", 128, 128, [300, 1024, 129, 2000]), ("fp32", 64, 32, [100, 333, 64])):
         wl = _wl("t", dtype, lens, 4, 2, d, block, 80, 12)
-        cfg = api.Config(block=block, n_init=block, window=block, step=2, theta=2.0)
+        cfg = api.Config(block=block, n_init=block, window=block, step=2, theta=4.5)
         run, worst = _run_and_check(api, wl, cfg, packed=True)
         assert worst["selected"] > 0
 
@@ -169,7 +169,7 @@ def test_fixed_batch_and_strided_layout(api):
     """B = 2 fixed-length batch; tensors given as [B, N, H, d] views (token-major memory)."""
     from parity_util import GpuRun, check_groups
     wl = _wl("t", "bf16", [1024, 1024], 4, 2, 128, 128, 90, 16)
-    cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=2.0)
+    cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=4.5)
     seqs = [synth.make_sequence(wl, s, signal="logit") for s in range(2)]
     run = GpuRun(api, seqs, cfg, "bf16", packed=False)
     for name in ("q", "k", "v", "out"):
@@ -201,7 +201,7 @@ def test_overflow_flag_and_capacity(api):
 def test_determinism(api):
     from parity_util import GpuRun
     wl = _wl("t", "bf16", [3000], 4, 2, 128, 128, 97, 40)
-    cfg = api.Config(block=128, n_init=128, window=128, step=4, theta=2.0)
+    cfg = api.Config(block=128, n_init=128, window=128, step=4, theta=5.0)
     seqs = [synth.make_sequence(wl, 0, signal="logit")]
     run = GpuRun(api, seqs, cfg, "bf16").stages()
     o1, i1, c1 = run.out.clone(), run.buf["idx"].clone(), run.buf["counts"].clone()
