@@ -165,7 +165,7 @@ int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
                                        (int)lds));
             attr_set = true;
         }
-        hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(128), lds, st, ea);
+        hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(256), lds, st, ea);
         AA_LAUNCHED("engine_bf16_kernel");
     } else {
         const size_t lds = engine_fp32_lds_bytes(k.d, k.bq);

@@ -7,13 +7,18 @@
 // and in what is read before / written after the loop.
 //
 // Shape of the computation (d = 128, b_q = 128, bf16 in, fp32 accumulate):
-//   work-group = one query block = 2 waves x 64 query rows;
-//   K/V tile   = 64 keys, double-buffered in LDS;
+//   work-group = one query block = 4 waves x 32 query rows, two work-groups per CU
+//   (two waves per SIMD, so one wave's softmax overlaps the other's MFMAs);
+//   K/V tile   = 64 keys, double-buffered in LDS, filled through registers;
 //   S^T = K Q^T  with v_mfma_f32_32x32x16_bf16 (keys are the M dimension, query
 //   rows the N dimension, so one lane owns one query row and the row max / sum
 //   are in-lane reductions plus one exchange between the wave's halves);
 //   O^T = V^T P^T with the same instruction; V is transposed on its way into LDS
 //   so that both operands are read with 16-byte LDS loads.
+// The running reference m of exp(s - m) is only raised when a row's maximum
+// exceeds it by more than 2^8; the accumulators (which live in AGPRs) are then
+// rescaled, otherwise they are left alone.  The true row maximum, which is the
+// anchor that stage 1 exports, is tracked separately.
 #include "aa_common.h"
 #include "aa_engine.h"
 
@@ -34,6 +39,7 @@ constexpr int VSTR = TK + 8;         // V^T tile row stride (elements): 144 B
 constexpr int KELEMS = TK * KSTR;
 constexpr int VELEMS = D * VSTR;
 constexpr int BUF = KELEMS + VELEMS; // one stage, in 2-byte elements
+constexpr float kRescaleLog2 = 8.f;  // raise the reference only for jumps above 2^8
 
 union Frag8 {
     bf16x8 v;
@@ -47,7 +53,7 @@ __device__ __forceinline__ float xhalf(float x) {  // value held by the lane 32 
 
 }  // namespace
 
-__global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
+__global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
     const KParams& p = a.p;
     const int tid = threadIdx.x;
@@ -60,7 +66,9 @@ __global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
     if (row0 >= sq.len) return;
     const int hk = wk.h / p.grp;
     const int g = wk.i / p.step;
-    const int rw = row0 + 64 * wave;                 // first row of this wave
+    const int rw = row0 + 32 * wave;                 // first row of this wave
+    const int r = rw + n;                            // this lane's query row
+    const bool rok = r < sq.len;
     const int rlast = min(row0 + BQ, sq.len) - 1;    // last row of the block
 
     // ---- tile sequence: [range 1: initial tokens][range 2: window .. diagonal][list chunks]
@@ -83,37 +91,35 @@ __global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
     const int nL = (cnt + TK - 1) / TK;
     const int nT = nA + nL;
 
-    const __bf16* qb = (const __bf16*)a.q;
     const unsigned short* kb_ = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, wk.b, hk, 0);
     const unsigned short* vb_ = (const unsigned short*)a.v + tok_offset(p, p.vs, sq, wk.b, hk, 0);
     const long long kst = p.ks[2], vst = p.vs[2];
 
-    // ---- loader role of this thread: 16-byte column chunk c of 8 keys
-    const int lc = tid & 15, ksid = tid >> 4;        // ksid = 2*sg + hh
-    int koff[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) koff[e] = 16 * (ksid >> 1) + 4 * (ksid & 1) + (e & 3) + 8 * (e >> 2);
+    // ---- loader role of this thread: 16-byte column chunk lc of the 4 keys of quad kq.
+    // quad (sg, a2, hh) holds keys 16 sg + 8 a2 + 4 hh + e; they sit at V^T positions
+    // 16 sg + 8 hh + 4 a2 + e, the order in which the accumulator layout hands out P.
+    const int lc = tid & 15, kq = tid >> 4;
+    const int sgq = kq >> 2, a2q = (kq >> 1) & 1, hhq = kq & 1;
+    const int kq0 = 16 * sgq + 8 * a2q + 4 * hhq;    // first key of the quad inside the tile
+    const int vpos = 16 * sgq + 8 * hhq + 4 * a2q;   // its position in a V^T row
 
     auto tile_start = [&](int t) -> int {            // first key of contiguous tile t (t < nA)
         return TK * (t < T1 ? t : t2s + (t - T1));
     };
     auto tile_keys = [&](int t, int* key) {
         if (t < nA) {
-            const int t0 = tile_start(t);
+            const int t0 = tile_start(t) + kq0;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) key[e] = min(t0 + koff[e], sq.len - 1);
+            for (int e = 0; e < 4; ++e) key[e] = min(t0 + e, sq.len - 1);
         } else {
-            const int* src = a.idx + lbase + (long long)(t - nA) * TK + koff[0];
-            const int4 x = *(const int4*)src;
-            const int4 y = *(const int4*)(src + 8);
+            const int4 x = *(const int4*)(a.idx + lbase + (long long)(t - nA) * TK + kq0);
             key[0] = x.x; key[1] = x.y; key[2] = x.z; key[3] = x.w;
-            key[4] = y.x; key[5] = y.y; key[6] = y.z; key[7] = y.w;
         }
     };
-    uint4 kreg[8], vreg[8];
+    uint4 kreg[4], vreg[4];
     auto tile_load = [&](const int* key) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int e = 0; e < 4; ++e) {
             kreg[e] = *(const uint4*)(kb_ + (long long)key[e] * kst + 8 * lc);
             vreg[e] = *(const uint4*)(vb_ + (long long)key[e] * vst + 8 * lc);
         }
@@ -122,76 +128,64 @@ __global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
         unsigned short* Ks = smem + buf * BUF;
         unsigned short* Vt = Ks + KELEMS;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) *(uint4*)(Ks + koff[e] * KSTR + 8 * lc) = kreg[e];
-        // transpose the 8 keys x 8 columns held by this thread: one 16 B row of V^T per column
-        const unsigned* vr = (const unsigned*)vreg;  // vr[4*e + a] = columns (2a, 2a+1) of key e
+        for (int e = 0; e < 4; ++e) *(uint4*)(Ks + (kq0 + e) * KSTR + 8 * lc) = kreg[e];
+        // transpose the 4 keys x 8 columns held by this thread: 8 bytes of a V^T row per column
+        const unsigned* vr = (const unsigned*)vreg;  // vr[4*e + j] = columns (2j, 2j+1) of key e
 #pragma unroll
-        for (int a2 = 0; a2 < 4; ++a2) {
-            uint4 lo, hi;
-            unsigned* plo = (unsigned*)&lo;
-            unsigned* phi = (unsigned*)&hi;
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const unsigned x = vr[4 * (2 * e2) + a2], y = vr[4 * (2 * e2 + 1) + a2];
-                plo[e2] = (x & 0xffffu) | (y << 16);
-                phi[e2] = (x >> 16) | (y & 0xffff0000u);
-            }
-            *(uint4*)(Vt + (8 * lc + 2 * a2) * VSTR + 8 * ksid) = lo;
-            *(uint4*)(Vt + (8 * lc + 2 * a2 + 1) * VSTR + 8 * ksid) = hi;
+        for (int j = 0; j < 4; ++j) {
+            const unsigned x0 = vr[j], x1 = vr[4 + j], x2 = vr[8 + j], x3 = vr[12 + j];
+            uint2 lo, hi;
+            lo.x = (x0 & 0xffffu) | (x1 << 16);
+            lo.y = (x2 & 0xffffu) | (x3 << 16);
+            hi.x = (x0 >> 16) | (x1 & 0xffff0000u);
+            hi.y = (x2 >> 16) | (x3 & 0xffff0000u);
+            *(uint2*)(Vt + (8 * lc + 2 * j) * VSTR + vpos) = lo;
+            *(uint2*)(Vt + (8 * lc + 2 * j + 1) * VSTR + vpos) = hi;
         }
     };
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane (n, hf) holds Q[row][16 ks + 8 hf .. +8)
-    Frag8 qf[2][8];
-#pragma unroll
-    for (int qa = 0; qa < 2; ++qa) {
-        const int r = rw + 32 * qa + n;
-        const bool ok = r < sq.len;
-        const __bf16* src = qb + tok_offset(p, p.qs, sq, wk.b, wk.h, ok ? r : 0);
+    Frag8 qf[8];
+    {
+        const __bf16* src = (const __bf16*)a.q + tok_offset(p, p.qs, sq, wk.b, wk.h, rok ? r : 0);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             uint4 x = *(const uint4*)(src + 16 * ks + 8 * hf);
-            if (!ok) x = make_uint4(0, 0, 0, 0);
-            qf[qa][ks].u = x;
+            if (!rok) x = make_uint4(0, 0, 0, 0);
+            qf[ks].u = x;
         }
     }
 
-    // ---- running state: m in raw dot-product units, l per lane (the two halves of a
-    // row are added at the end), O^T accumulators
+    // ---- running state, raw dot-product units: reference mref of the exponentials, true
+    // maximum mtrue, per-lane partial row sum l (the two halves of a row are added at the
+    // end), O^T accumulators
     const float c2 = p.sigma * 1.4426950408889634f;  // exp(sigma*x) = exp2(c2*x)
-    float m[2], l[2];
-    floatx16 o[4][2];
+    const long long ri = row_index(p, sq, wk.b, wk.h, rok ? r : row0);
+    float mref, mtrue, l;
+    floatx16 o[4];
     if (a.flags & kEngLoadState) {
+        mref = a.Min[ri] / p.sigma;
+        mtrue = mref;
+        l = hf == 0 ? a.Lin[ri] : 0.f;
+        const float* acc = a.Accin + ri * D;
 #pragma unroll
-        for (int qa = 0; qa < 2; ++qa) {
-            const int r = rw + 32 * qa + n;
-            const bool ok = r < sq.len;
-            const long long ri = row_index(p, sq, wk.b, wk.h, ok ? r : row0);
-            m[qa] = a.Min[ri] / p.sigma;
-            l[qa] = hf == 0 ? a.Lin[ri] : 0.f;
-            const float* acc = a.Accin + ri * D;
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const float4 x = *(const float4*)(acc + 32 * db + 8 * v4 + 4 * hf);
-                    o[db][qa][4 * v4 + 0] = x.x; o[db][qa][4 * v4 + 1] = x.y;
-                    o[db][qa][4 * v4 + 2] = x.z; o[db][qa][4 * v4 + 3] = x.w;
-                }
-        }
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const float4 x = *(const float4*)(acc + 32 * db + 8 * v4 + 4 * hf);
+                o[db][4 * v4 + 0] = x.x; o[db][4 * v4 + 1] = x.y;
+                o[db][4 * v4 + 2] = x.z; o[db][4 * v4 + 3] = x.w;
+            }
     } else {
+        mref = -INFINITY; mtrue = -INFINITY; l = 0.f;
 #pragma unroll
-        for (int qa = 0; qa < 2; ++qa) {
-            m[qa] = -INFINITY; l[qa] = 0.f;
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][qa][v] = 0.f;
-        }
+            for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
     }
 
     // ---- pipeline prologue
-    int keys[8];
+    int keys[4];
     if (nT > 0) {
         tile_keys(0, keys);
         tile_load(keys);
@@ -208,22 +202,18 @@ __global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
         const unsigned short* Ks = smem + (t & 1) * BUF;
         const unsigned short* Vt = Ks + KELEMS;
 
-        // S^T = K Q^T : s[kb][qa], 32 keys x 32 rows each
-        floatx16 s[2][2];
+        // S^T = K Q^T : s[kb], 32 keys x 32 rows each
+        floatx16 s[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int qa = 0; qa < 2; ++qa)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s[kb][qa][v] = 0.f;
+            for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 const bf16x8 kf = *(const bf16x8*)(Ks + (32 * kb + n) * KSTR + 16 * ks + 8 * hf);
-#pragma unroll
-                for (int qa = 0; qa < 2; ++qa)
-                    s[kb][qa] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qa][ks].v, s[kb][qa], 0, 0, 0);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks].v, s[kb], 0, 0, 0);
             }
 
         // masks: only tiles that touch a region boundary, the diagonal or a list tail
@@ -234,14 +224,10 @@ __global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int qa = 0; qa < 2; ++qa) {
-                        const int r = rw + 32 * qa + n;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int j = t0 + 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
-                            const bool ok = (j <= r) && (j < ninit || j >= W);
-                            if (!ok) s[kb][qa][v] = -INFINITY;
-                        }
+                    for (int v = 0; v < 16; ++v) {
+                        const int j = t0 + 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
+                        const bool ok = (j <= r) && (j < ninit || j >= W);
+                        if (!ok) s[kb][v] = -INFINITY;
                     }
             }
         } else if (t == nT - 1 && (cnt & (TK - 1))) {
@@ -249,46 +235,42 @@ __global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int qa = 0; qa < 2; ++qa)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int pos = 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
-                        if (pos >= rem) s[kb][qa][v] = -INFINITY;
-                    }
+                for (int v = 0; v < 16; ++v) {
+                    const int pos = 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
+                    if (pos >= rem) s[kb][v] = -INFINITY;
+                }
         }
 
-        // online softmax per query row (one lane pair per row)
-        Frag8 pf[2][2][2];  // [kb][s16][qa]
+        // online softmax of this lane's query row (the other half of the row is 32 lanes away)
+        float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-        for (int qa = 0; qa < 2; ++qa) {
-            float mx = s[0][qa][0];
-#pragma unroll
-            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[0][qa][v]);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[1][qa][v]);
-            mx = fmaxf(mx, xhalf(mx));
-            const float mnew = fmaxf(m[qa], mx);
-            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float alpha = __builtin_amdgcn_exp2f((m[qa] - muse) * c2);
-            const float mc = muse * c2;
-            m[qa] = mnew;
-            float rs = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; v += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][qa][v], c2, -mc));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][qa][v + 1], c2, -mc));
-                    rs += p0 + p1;
-                    floatx2 pp = {p0, p1};
-                    pf[kb][v >> 3][qa].h[(v & 7) >> 1] = __builtin_convertvector(pp, bf16x2);
-                }
-            l[qa] = l[qa] * alpha + rs;
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s[0][v], s[1][v]));
+        mx = fmaxf(mx, xhalf(mx));
+        mtrue = fmaxf(mtrue, mx);
+        if (__any((mx - mref) * c2 > kRescaleLog2)) {       // rare after the first tiles
+            const float mnew = fmaxf(mref, mx);
+            const float alpha = (mnew == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mnew) * c2);
+            mref = mnew;
+            l *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][qa][v] *= alpha;
+                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         }
+        const float mc = (mref == -INFINITY) ? 0.f : mref * c2;
+        Frag8 pf[2][2];  // [kb][s16]
+        float rs = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][v], c2, -mc));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][v + 1], c2, -mc));
+                rs += p0 + p1;
+                floatx2 pp = {p0, p1};
+                pf[kb][v >> 3].h[(v & 7) >> 1] = __builtin_convertvector(pp, bf16x2);
+            }
+        l += rs;
 
         // O^T += V^T P^T
 #pragma unroll
@@ -296,10 +278,7 @@ __global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
                 const bf16x8 vf = *(const bf16x8*)(Vt + (32 * db + n) * VSTR + 16 * sg + 8 * hf);
-#pragma unroll
-                for (int qa = 0; qa < 2; ++qa)
-                    o[db][qa] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sg >> 1][sg & 1][qa].v,
-                                                                         o[db][qa], 0, 0, 0);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sg >> 1][sg & 1].v, o[db], 0, 0, 0);
             }
 
         if (t + 1 < nT) tile_store((t + 1) & 1);
@@ -307,57 +286,51 @@ __global__ __launch_bounds__(128) void engine_bf16_kernel(EngineArgs a) {
     }
 
     // ---- epilogue
-    float red_m = 0.f;  // sum of this wave's anchors over valid rows (for the pooled anchor)
+    const float lt = l + xhalf(l);                   // row sum relative to mref
+    if (a.flags & kEngStoreState) {
+        // exported state is relative to the true maximum (Algorithm 1's m, l, acc)
+        const float down = (mref == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mtrue) * c2);
+        const float ms = mtrue * p.sigma;
+        if (rok && hf == 0) { a.Mout[ri] = ms; a.Lout[ri] = lt * down; }
+        if (rok && a.Accout) {
+            float* acc = a.Accout + ri * D;
 #pragma unroll
-    for (int qa = 0; qa < 2; ++qa) {
-        const int r = rw + 32 * qa + n;
-        const bool ok = r < sq.len;
-        const float lt = l[qa] + xhalf(l[qa]);
-        const float ms = m[qa] * p.sigma;
-        const long long ri = row_index(p, sq, wk.b, wk.h, ok ? r : row0);
-        if (a.flags & kEngStoreState) {
-            if (ok && hf == 0) { a.Mout[ri] = ms; a.Lout[ri] = lt; red_m += ms; }
-            if (ok && a.Accout) {
-                float* acc = a.Accout + ri * D;
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int v4 = 0; v4 < 4; ++v4)
-                        *(float4*)(acc + 32 * db + 8 * v4 + 4 * hf) =
-                            make_float4(o[db][qa][4 * v4], o[db][qa][4 * v4 + 1], o[db][qa][4 * v4 + 2],
-                                        o[db][qa][4 * v4 + 3]);
-            }
+                for (int v4 = 0; v4 < 4; ++v4)
+                    *(float4*)(acc + 32 * db + 8 * v4 + 4 * hf) =
+                        make_float4(o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
+                                    o[db][4 * v4 + 3] * down);
         }
-        if (a.flags & kEngStoreOut) {
-            const float inv = 1.f / lt;
-            if (ok) {
-                unsigned short* dst = (unsigned short*)a.out + tok_offset(p, p.os, sq, wk.b, wk.h, r);
+        if (a.xa) {
+            // pooled anchor of the block: mean of M over its rows (Algorithm 2, avgpool of the anchor)
+            float red_m = (rok && hf == 0) ? ms : 0.f;
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int v4 = 0; v4 < 4; ++v4) {
-                        floatx2 x0 = {o[db][qa][4 * v4] * inv, o[db][qa][4 * v4 + 1] * inv};
-                        floatx2 x1 = {o[db][qa][4 * v4 + 2] * inv, o[db][qa][4 * v4 + 3] * inv};
-                        union { bf16x2 h[2]; uint2 u; } pk;
-                        pk.h[0] = __builtin_convertvector(x0, bf16x2);
-                        pk.h[1] = __builtin_convertvector(x1, bf16x2);
-                        *(uint2*)(dst + 32 * db + 8 * v4 + 4 * hf) = pk.u;
-                    }
-                if (a.lse && hf == 0) a.lse[ri] = ms + __logf(lt);
+            for (int off = 32; off >= 1; off >>= 1) red_m += __shfl_xor(red_m, off, 64);
+            float* red = (float*)smem;               // all tile reads are behind the last barrier
+            if (lane == 0) red[wave] = red_m;
+            __syncthreads();
+            if (tid == 0) {
+                const int nrows = rlast - row0 + 1;
+                a.xa[blk_index(p, sq, wk.b, wk.h, wk.i)] = (red[0] + red[1] + red[2] + red[3]) / (float)nrows;
             }
         }
     }
-    if ((a.flags & kEngStoreState) && a.xa) {
-        // pooled anchor of the block: mean of M over its rows (Algorithm 2, avgpool of the anchor)
-        float* red = (float*)smem;                   // all tile reads are behind the last barrier
+    if ((a.flags & kEngStoreOut) && rok) {
+        const float inv = 1.f / lt;
+        unsigned short* dst = (unsigned short*)a.out + tok_offset(p, p.os, sq, wk.b, wk.h, r);
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) red_m += __shfl_xor(red_m, off, 64);
-        if (lane == 0) red[wave] = red_m;
-        __syncthreads();
-        if (tid == 0) {
-            const int nrows = rlast - row0 + 1;
-            a.xa[blk_index(p, sq, wk.b, wk.h, wk.i)] = (red[0] + red[1]) / (float)nrows;
-        }
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                floatx2 x0 = {o[db][4 * v4] * inv, o[db][4 * v4 + 1] * inv};
+                floatx2 x1 = {o[db][4 * v4 + 2] * inv, o[db][4 * v4 + 3] * inv};
+                union { bf16x2 h[2]; uint2 u; } pk;
+                pk.h[0] = __builtin_convertvector(x0, bf16x2);
+                pk.h[1] = __builtin_convertvector(x1, bf16x2);
+                *(uint2*)(dst + 32 * db + 8 * v4 + 4 * hf) = pk.u;
+            }
+        if (a.lse && hf == 0) a.lse[ri] = mref * p.sigma + __logf(lt);
     }
 }
 
