@@ -35,17 +35,23 @@ constexpr int D = 128;
 constexpr int BQ = 128;
 constexpr int TK = 64;               // keys per tile
 constexpr int KSTR = D + 8;          // K tile row stride (elements): 272 B, conflict-free 16 B reads
-constexpr int VSTR = TK + 8;         // V^T tile row stride (elements): 144 B
+constexpr int VSTR = TK + 8;         // V^T tile row stride (elements): 144 B, plus 16 B of skew per 16 rows
 constexpr int KELEMS = TK * KSTR;
-constexpr int VELEMS = D * VSTR;
+constexpr int VELEMS = D * VSTR + (D / 16) * 8;
 constexpr int BUF = KELEMS + VELEMS; // one stage, in 2-byte elements
 constexpr float kRescaleLog2 = 8.f;  // raise the reference only for jumps above 2^8
+constexpr floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-union Frag8 {
-    bf16x8 v;
-    bf16x2 h[4];
-    uint4 u;
-};
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+
+// Element offset of V^T row `row`: with the skew both the 16-byte operand reads (32 lanes,
+// consecutive rows) and the 8-byte transposed writes (16 lanes, rows 8 apart) spread over all banks.
+__device__ __forceinline__ int vt_row(int row) { return row * VSTR + (row >> 4) * 8; }
 
 __device__ __forceinline__ float xhalf(float x) {  // value held by the lane 32 away
     return __shfl_xor(x, 32, 64);
@@ -112,47 +118,46 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) key[e] = min(t0 + e, sq.len - 1);
         } else {
-            const int4 x = *(const int4*)(a.idx + lbase + (long long)(t - nA) * TK + kq0);
+            const intx4 x = *(const intx4*)(a.idx + lbase + (long long)(t - nA) * TK + kq0);
             key[0] = x.x; key[1] = x.y; key[2] = x.z; key[3] = x.w;
         }
     };
-    uint4 kreg[4], vreg[4];
+    uintx4 kreg[4], vreg[4];
     auto tile_load = [&](const int* key) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            kreg[e] = *(const uint4*)(kb_ + (long long)key[e] * kst + 8 * lc);
-            vreg[e] = *(const uint4*)(vb_ + (long long)key[e] * vst + 8 * lc);
+            kreg[e] = *(const uintx4*)(kb_ + (long long)key[e] * kst + 8 * lc);
+            vreg[e] = *(const uintx4*)(vb_ + (long long)key[e] * vst + 8 * lc);
         }
     };
     auto tile_store = [&](int buf) {
         unsigned short* Ks = smem + buf * BUF;
         unsigned short* Vt = Ks + KELEMS;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) *(uint4*)(Ks + (kq0 + e) * KSTR + 8 * lc) = kreg[e];
+        for (int e = 0; e < 4; ++e) *(uintx4*)(Ks + (kq0 + e) * KSTR + 8 * lc) = kreg[e];
         // transpose the 4 keys x 8 columns held by this thread: 8 bytes of a V^T row per column
-        const unsigned* vr = (const unsigned*)vreg;  // vr[4*e + j] = columns (2j, 2j+1) of key e
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const unsigned x0 = vr[j], x1 = vr[4 + j], x2 = vr[8 + j], x3 = vr[12 + j];
-            uint2 lo, hi;
-            lo.x = (x0 & 0xffffu) | (x1 << 16);
-            lo.y = (x2 & 0xffffu) | (x3 << 16);
-            hi.x = (x0 >> 16) | (x1 & 0xffff0000u);
-            hi.y = (x2 >> 16) | (x3 & 0xffff0000u);
-            *(uint2*)(Vt + (8 * lc + 2 * j) * VSTR + vpos) = lo;
-            *(uint2*)(Vt + (8 * lc + 2 * j + 1) * VSTR + vpos) = hi;
-        }
+        auto put = [&](int j, unsigned x0, unsigned x1, unsigned x2, unsigned x3) {
+            // x_e = columns (2j, 2j+1) of key e
+            const uintx2 lo = {(x0 & 0xffffu) | (x1 << 16), (x2 & 0xffffu) | (x3 << 16)};
+            const uintx2 hi = {(x0 >> 16) | (x1 & 0xffff0000u), (x2 >> 16) | (x3 & 0xffff0000u)};
+            *(uintx2*)(Vt + vt_row(8 * lc + 2 * j) + vpos) = lo;
+            *(uintx2*)(Vt + vt_row(8 * lc + 2 * j + 1) + vpos) = hi;
+        };
+        put(0, vreg[0].x, vreg[1].x, vreg[2].x, vreg[3].x);
+        put(1, vreg[0].y, vreg[1].y, vreg[2].y, vreg[3].y);
+        put(2, vreg[0].z, vreg[1].z, vreg[2].z, vreg[3].z);
+        put(3, vreg[0].w, vreg[1].w, vreg[2].w, vreg[3].w);
     };
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane (n, hf) holds Q[row][16 ks + 8 hf .. +8)
-    Frag8 qf[8];
+    bf16x8 qf[8];
     {
         const __bf16* src = (const __bf16*)a.q + tok_offset(p, p.qs, sq, wk.b, wk.h, rok ? r : 0);
+        const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            uint4 x = *(const uint4*)(src + 16 * ks + 8 * hf);
-            if (!rok) x = make_uint4(0, 0, 0, 0);
-            qf[ks].u = x;
+            const bf16x8 x = *(const bf16x8*)(src + 16 * ks + 8 * hf);
+            qf[ks] = rok ? x : zero8;
         }
     }
 
@@ -172,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
-                const float4 x = *(const float4*)(acc + 32 * db + 8 * v4 + 4 * hf);
+                const floatx4 x = *(const floatx4*)(acc + 32 * db + 8 * v4 + 4 * hf);
                 o[db][4 * v4 + 0] = x.x; o[db][4 * v4 + 1] = x.y;
                 o[db][4 * v4 + 2] = x.z; o[db][4 * v4 + 3] = x.w;
             }
@@ -205,15 +210,11 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         // S^T = K Q^T : s[kb], 32 keys x 32 rows each
         floatx16 s[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-#pragma unroll
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 const bf16x8 kf = *(const bf16x8*)(Ks + (32 * kb + n) * KSTR + 16 * ks + 8 * hf);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks].v, s[kb], 0, 0, 0);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? kZero16 : s[kb], 0, 0, 0);
             }
 
         // masks: only tiles that touch a region boundary, the diagonal or a list tail
@@ -221,13 +222,15 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             const int t0 = tile_start(t);
             const bool interior = (t0 + TK - 1 <= rw) && (t0 + TK <= ninit || t0 >= W);
             if (!interior) {
+                // key j = t0 + jl is visible to row r iff j <= r and (j < ninit or j >= W)
+                const int jr = r - t0, jn = ninit - t0, jw = W - t0;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const int j = t0 + 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
-                        const bool ok = (j <= r) && (j < ninit || j >= W);
-                        if (!ok) s[kb][v] = -INFINITY;
+                        const int jl = 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
+                        const bool ok = (jl <= jr) & ((jl < jn) | (jl >= jw));
+                        s[kb][v] = ok ? s[kb][v] : -INFINITY;
                     }
             }
         } else if (t == nT - 1 && (cnt & (TK - 1))) {
@@ -237,7 +240,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int pos = 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
-                    if (pos >= rem) s[kb][v] = -INFINITY;
+                    s[kb][v] = pos < rem ? s[kb][v] : -INFINITY;
                 }
         }
 
@@ -258,17 +261,19 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
                 for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         }
         const float mc = (mref == -INFINITY) ? 0.f : mref * c2;
-        Frag8 pf[2][2];  // [kb][s16]
+        bf16x8 pf[2][2];  // [kb][s16]
         float rs = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][v], c2, -mc));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][v + 1], c2, -mc));
-                rs += p0 + p1;
-                floatx2 pp = {p0, p1};
-                pf[kb][v >> 3].h[(v & 7) >> 1] = __builtin_convertvector(pp, bf16x2);
+            for (int h8 = 0; h8 < 2; ++h8) {
+                floatx8 pv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * h8 + e], c2, -mc));
+                    rs += pv[e];
+                }
+                pf[kb][h8] = __builtin_convertvector(pv, bf16x8);
             }
         l += rs;
 
@@ -277,8 +282,8 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         for (int sg = 0; sg < 4; ++sg)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                const bf16x8 vf = *(const bf16x8*)(Vt + (32 * db + n) * VSTR + 16 * sg + 8 * hf);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sg >> 1][sg & 1].v, o[db], 0, 0, 0);
+                const bf16x8 vf = *(const bf16x8*)(Vt + vt_row(32 * db + n) + 16 * sg + 8 * hf);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sg >> 1][sg & 1], o[db], 0, 0, 0);
             }
 
         if (t + 1 < nT) tile_store((t + 1) & 1);
@@ -298,9 +303,9 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int v4 = 0; v4 < 4; ++v4)
-                    *(float4*)(acc + 32 * db + 8 * v4 + 4 * hf) =
-                        make_float4(o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
-                                    o[db][4 * v4 + 3] * down);
+                    *(floatx4*)(acc + 32 * db + 8 * v4 + 4 * hf) =
+                        floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
+                                o[db][4 * v4 + 3] * down};
         }
         if (a.xa) {
             // pooled anchor of the block: mean of M over its rows (Algorithm 2, avgpool of the anchor)
@@ -323,12 +328,9 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
-                floatx2 x0 = {o[db][4 * v4] * inv, o[db][4 * v4 + 1] * inv};
-                floatx2 x1 = {o[db][4 * v4 + 2] * inv, o[db][4 * v4 + 3] * inv};
-                union { bf16x2 h[2]; uint2 u; } pk;
-                pk.h[0] = __builtin_convertvector(x0, bf16x2);
-                pk.h[1] = __builtin_convertvector(x1, bf16x2);
-                *(uint2*)(dst + 32 * db + 8 * v4 + 4 * hf) = pk.u;
+                const floatx4 x = {o[db][4 * v4] * inv, o[db][4 * v4 + 1] * inv, o[db][4 * v4 + 2] * inv,
+                                   o[db][4 * v4 + 3] * inv};
+                *(bf16x4*)(dst + 32 * db + 8 * v4 + 4 * hf) = __builtin_convertvector(x, bf16x4);
             }
         if (a.lse && hf == 0) a.lse[ri] = mref * p.sigma + __logf(lt);
     }
