@@ -63,7 +63,8 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
     const KParams& p = a.p;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
     const int n = lane & 31, hf = lane >> 5;
 
     const Work wk = decode_work(p, p.nblk_max, blockIdx.x);
@@ -97,9 +98,14 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     const int nL = (cnt + TK - 1) / TK;
     const int nT = nA + nL;
 
+    // K / V rows of this KV head are fetched with raw buffer loads: scalar base, 32-bit byte offsets
     const unsigned short* kb_ = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, wk.b, hk, 0);
     const unsigned short* vb_ = (const unsigned short*)a.v + tok_offset(p, p.vs, sq, wk.b, hk, 0);
-    const long long kst = p.ks[2], vst = p.vs[2];
+    const unsigned kstb = (unsigned)p.ks[2] * 2u, vstb = (unsigned)p.vs[2] * 2u;   // token strides in bytes
+    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)kb_, 0, (int)((unsigned)(sq.len - 1) * kstb + 2u * D), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)vb_, 0, (int)((unsigned)(sq.len - 1) * vstb + 2u * D), 0x00020000);
 
     // ---- loader role of this thread: 16-byte column chunk lc of the 4 keys of quad kq.
     // quad (sg, a2, hh) holds keys 16 sg + 8 a2 + 4 hh + e; they sit at V^T positions
@@ -126,8 +132,8 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     auto tile_load = [&](const int* key) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            kreg[e] = *(const uintx4*)(kb_ + (long long)key[e] * kst + 8 * lc);
-            vreg[e] = *(const uintx4*)(vb_ + (long long)key[e] * vst + 8 * lc);
+            kreg[e] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)((unsigned)key[e] * kstb + 16u * lc), 0, 0);
+            vreg[e] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)((unsigned)key[e] * vstb + 16u * lc), 0, 0);
         }
     };
     auto tile_store = [&](int buf) {
@@ -138,8 +144,9 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         // transpose the 4 keys x 8 columns held by this thread: 8 bytes of a V^T row per column
         auto put = [&](int j, unsigned x0, unsigned x1, unsigned x2, unsigned x3) {
             // x_e = columns (2j, 2j+1) of key e
-            const uintx2 lo = {(x0 & 0xffffu) | (x1 << 16), (x2 & 0xffffu) | (x3 << 16)};
-            const uintx2 hi = {(x0 >> 16) | (x1 & 0xffff0000u), (x2 >> 16) | (x3 & 0xffff0000u)};
+            // v_perm_b32 picks bytes from {src0 (bytes 4..7), src1 (bytes 0..3)}
+            const uintx2 lo = {__builtin_amdgcn_perm(x1, x0, 0x05040100u), __builtin_amdgcn_perm(x3, x2, 0x05040100u)};
+            const uintx2 hi = {__builtin_amdgcn_perm(x1, x0, 0x07060302u), __builtin_amdgcn_perm(x3, x2, 0x07060302u)};
             *(uintx2*)(Vt + vt_row(8 * lc + 2 * j) + vpos) = lo;
             *(uintx2*)(Vt + vt_row(8 * lc + 2 * j + 1) + vpos) = hi;
         };
@@ -165,6 +172,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     // maximum mtrue, per-lane partial row sum l (the two halves of a row are added at the
     // end), O^T accumulators
     const float c2 = p.sigma * 1.4426950408889634f;  // exp(sigma*x) = exp2(c2*x)
+    const float rescale_gap = kRescaleLog2 / c2;
     const long long ri = row_index(p, sq, wk.b, wk.h, rok ? r : row0);
     float mref, mtrue, l;
     floatx16 o[4];
@@ -207,42 +215,50 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         const unsigned short* Ks = smem + (t & 1) * BUF;
         const unsigned short* Vt = Ks + KELEMS;
 
-        // S^T = K Q^T : s[kb], 32 keys x 32 rows each
+        // S^T = K Q^T : s[kb], 32 keys x 32 rows each.  Masks (tiles that touch a region
+        // boundary, the diagonal or a list tail) enter as the initial accumulator: 0 for a
+        // visible (key, row) pair, -inf otherwise; the common unmasked tile starts from literal 0.
         floatx16 s[2];
+        int mode = 0, t0 = 0;
+        if (t < nA) {
+            t0 = tile_start(t);
+            const bool interior = (t0 + TK - 1 <= rw) && (t0 + TK <= ninit || t0 >= W);
+            mode = interior ? 0 : 1;
+        } else if (t == nT - 1 && (cnt & (TK - 1))) {
+            mode = 2;
+        }
+        if (mode == 0) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+            for (int kb = 0; kb < 2; ++kb) {
+                const bf16x8 kf = *(const bf16x8*)(Ks + (32 * kb + n) * KSTR + 8 * hf);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0], kZero16, 0, 0, 0);
+            }
+        } else {
+            // key j = t0 + jl is visible to row r iff j <= r and (j < ninit or j >= W);
+            // entry jl of the last list chunk is real iff jl < rem
+            const int jr = mode == 1 ? r - t0 : cnt - (t - nA) * TK - 1;
+            const int jn = mode == 1 ? ninit - t0 : TK;
+            const int jw = W - t0;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                floatx16 bias;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int jl = 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
+                    const bool ok = (jl <= jr) & ((jl < jn) | (jl >= jw));
+                    bias[v] = ok ? 0.f : -INFINITY;
+                }
+                const bf16x8 kf = *(const bf16x8*)(Ks + (32 * kb + n) * KSTR + 8 * hf);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0], bias, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int ks = 1; ks < 8; ++ks)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 const bf16x8 kf = *(const bf16x8*)(Ks + (32 * kb + n) * KSTR + 16 * ks + 8 * hf);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? kZero16 : s[kb], 0, 0, 0);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
             }
-
-        // masks: only tiles that touch a region boundary, the diagonal or a list tail
-        if (t < nA) {
-            const int t0 = tile_start(t);
-            const bool interior = (t0 + TK - 1 <= rw) && (t0 + TK <= ninit || t0 >= W);
-            if (!interior) {
-                // key j = t0 + jl is visible to row r iff j <= r and (j < ninit or j >= W)
-                const int jr = r - t0, jn = ninit - t0, jw = W - t0;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int jl = 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
-                        const bool ok = (jl <= jr) & ((jl < jn) | (jl >= jw));
-                        s[kb][v] = ok ? s[kb][v] : -INFINITY;
-                    }
-            }
-        } else if (t == nT - 1 && (cnt & (TK - 1))) {
-            const int rem = cnt - (t - nA) * TK;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int pos = 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
-                    s[kb][v] = pos < rem ? s[kb][v] : -INFINITY;
-                }
-        }
 
         // online softmax of this lane's query row (the other half of the row is 32 lanes away)
         float mx = fmaxf(s[0][0], s[1][0]);
@@ -250,7 +266,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s[0][v], s[1][v]));
         mx = fmaxf(mx, xhalf(mx));
         mtrue = fmaxf(mtrue, mx);
-        if (__any((mx - mref) * c2 > kRescaleLog2)) {       // rare after the first tiles
+        if (__any(mx > mref + rescale_gap)) {                 // rare after the first tiles
             const float mnew = fmaxf(mref, mx);
             const float alpha = (mnew == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mnew) * c2);
             mref = mnew;
