@@ -9,12 +9,17 @@
 // Shape of the computation (d = 128, b_q = 128, bf16 in, fp32 accumulate):
 //   work-group = one query block = 4 waves x 32 query rows, two work-groups per CU
 //   (two waves per SIMD, so one wave's softmax overlaps the other's MFMAs);
-//   K/V tile   = 64 keys, double-buffered in LDS, filled through registers;
+//   K/V tile   = 64 keys, double-buffered in LDS, filled by 16-byte direct-to-LDS buffer
+//   loads (no staging registers; a gathered row and a contiguous row cost the same);
 //   S^T = K Q^T  with v_mfma_f32_32x32x16_bf16 (keys are the M dimension, query
 //   rows the N dimension, so one lane owns one query row and the row max / sum
 //   are in-lane reductions plus one exchange between the wave's halves);
-//   O^T = V^T P^T with the same instruction; V is transposed on its way into LDS
-//   so that both operands are read with 16-byte LDS loads.
+//   O^T = V^T P^T with the same instruction; V stays row-major in LDS and its operand
+//   is read with the transposing LDS load ds_read_b64_tr_b16.
+// LDS layout of a tile: a direct-to-LDS load writes the 64 lanes' 16 bytes to consecutive
+// addresses, i.e. 1 KB = four 256-byte rows per instruction ("group").  Key kk of the tile
+// sits in group kk % 16, row kk / 16; groups are padded (K: 16 B, V: 64 B) so that the 16
+// lanes of an operand read fall into different banks.
 // The running reference m of exp(s - m) is only raised when a row's maximum
 // exceeds it by more than 2^8; the accumulators (which live in AGPRs) are then
 // rescaled, otherwise they are left alone.  The true row maximum, which is the
@@ -34,11 +39,11 @@ namespace {
 constexpr int D = 128;
 constexpr int BQ = 128;
 constexpr int TK = 64;               // keys per tile
-constexpr int KSTR = D + 8;          // K tile row stride (elements): 272 B, conflict-free 16 B reads
-constexpr int VSTR = TK + 8;         // V^T tile row stride (elements): 144 B, plus 16 B of skew per 16 rows
-constexpr int KELEMS = TK * KSTR;
-constexpr int VELEMS = D * VSTR + (D / 16) * 8;
-constexpr int BUF = KELEMS + VELEMS; // one stage, in 2-byte elements
+constexpr int KGRP = 1024 + 16;      // bytes per K group: 4 rows + pad
+constexpr int VGRP = 1024 + 64;      // bytes per V group
+constexpr int KBYTES = 16 * KGRP;
+constexpr int VBYTES = 16 * VGRP;
+constexpr int BUFB = KBYTES + VBYTES; // one stage, bytes
 constexpr float kRescaleLog2 = 8.f;  // raise the reference only for jumps above 2^8
 constexpr floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
@@ -49,9 +54,12 @@ typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
 
-// Element offset of V^T row `row`: with the skew both the 16-byte operand reads (32 lanes,
-// consecutive rows) and the 8-byte transposed writes (16 lanes, rows 8 apart) spread over all banks.
-__device__ __forceinline__ int vt_row(int row) { return row * VSTR + (row >> 4) * 8; }
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef short shortx8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) void lds_void;
+
+// s_waitcnt vmcnt(0) only (gfx9 encoding: expcnt and lgkmcnt fields left at their maxima)
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 __device__ __forceinline__ float xhalf(float x) {  // value held by the lane 32 away
     return __shfl_xor(x, 32, 64);
@@ -107,13 +115,12 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
         (void*)vb_, 0, (int)((unsigned)(sq.len - 1) * vstb + 2u * D), 0x00020000);
 
-    // ---- loader role of this thread: 16-byte column chunk lc of the 4 keys of quad kq.
-    // quad (sg, a2, hh) holds keys 16 sg + 8 a2 + 4 hh + e; they sit at V^T positions
-    // 16 sg + 8 hh + 4 a2 + e, the order in which the accumulator layout hands out P.
-    const int lc = tid & 15, kq = tid >> 4;
-    const int sgq = kq >> 2, a2q = (kq >> 1) & 1, hhq = kq & 1;
-    const int kq0 = 16 * sgq + 8 * a2q + 4 * hhq;    // first key of the quad inside the tile
-    const int vpos = 16 * sgq + 8 * hhq + 4 * a2q;   // its position in a V^T row
+    // ---- loader role of this wave: groups 4 wave .. 4 wave + 3 of every tile.  In the load of
+    // group gi lane l fetches the 16-byte chunk l % 16 of key 16 (l / 16) + gi of the tile, so each
+    // lane deals with the 4 consecutive keys 16 (l / 16) + 4 wave + j.
+    const int lch = lane & 15;
+    const int kq0 = 16 * (lane >> 4) + 4 * wave;     // first of this lane's 4 keys inside the tile
+    char* const smem_b = (char*)smem;
 
     auto tile_start = [&](int t) -> int {            // first key of contiguous tile t (t < nA)
         return TK * (t < T1 ? t : t2s + (t - T1));
@@ -128,32 +135,17 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             key[0] = x.x; key[1] = x.y; key[2] = x.z; key[3] = x.w;
         }
     };
-    uintx4 kreg[4], vreg[4];
-    auto tile_load = [&](const int* key) {
+    auto tile_load = [&](const int* key, int buf) {  // asynchronous: completion is awaited by wait_vmem()
+        char* Kb = smem_b + buf * BUFB;
+        char* Vb = Kb + KBYTES;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            kreg[e] = __builtin_amdgcn_raw_buffer_load_b128(krs, (int)((unsigned)key[e] * kstb + 16u * lc), 0, 0);
-            vreg[e] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (int)((unsigned)key[e] * vstb + 16u * lc), 0, 0);
+        for (int j = 0; j < 4; ++j) {
+            const int gi = 4 * wave + j;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(Kb + gi * KGRP), 16,
+                                                     (int)((unsigned)key[j] * kstb + 16u * lch), 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(vrs, (lds_void*)(Vb + gi * VGRP), 16,
+                                                     (int)((unsigned)key[j] * vstb + 16u * lch), 0, 0, 0);
         }
-    };
-    auto tile_store = [&](int buf) {
-        unsigned short* Ks = smem + buf * BUF;
-        unsigned short* Vt = Ks + KELEMS;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) *(uintx4*)(Ks + (kq0 + e) * KSTR + 8 * lc) = kreg[e];
-        // transpose the 4 keys x 8 columns held by this thread: 8 bytes of a V^T row per column
-        auto put = [&](int j, unsigned x0, unsigned x1, unsigned x2, unsigned x3) {
-            // x_e = columns (2j, 2j+1) of key e
-            // v_perm_b32 picks bytes from {src0 (bytes 4..7), src1 (bytes 0..3)}
-            const uintx2 lo = {__builtin_amdgcn_perm(x1, x0, 0x05040100u), __builtin_amdgcn_perm(x3, x2, 0x05040100u)};
-            const uintx2 hi = {__builtin_amdgcn_perm(x1, x0, 0x07060302u), __builtin_amdgcn_perm(x3, x2, 0x07060302u)};
-            *(uintx2*)(Vt + vt_row(8 * lc + 2 * j) + vpos) = lo;
-            *(uintx2*)(Vt + vt_row(8 * lc + 2 * j + 1) + vpos) = hi;
-        };
-        put(0, vreg[0].x, vreg[1].x, vreg[2].x, vreg[3].x);
-        put(1, vreg[0].y, vreg[1].y, vreg[2].y, vreg[3].y);
-        put(2, vreg[0].z, vreg[1].z, vreg[2].z, vreg[3].z);
-        put(3, vreg[0].w, vreg[1].w, vreg[2].w, vreg[3].w);
     };
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane (n, hf) holds Q[row][16 ks + 8 hf .. +8)
@@ -201,19 +193,25 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     int keys[4];
     if (nT > 0) {
         tile_keys(0, keys);
-        tile_load(keys);
+        tile_load(keys, 0);
         if (nT > 1) tile_keys(1, keys);
-        tile_store(0);
     }
+    wait_vmem();
     __syncthreads();
+
+    // operand addresses inside a stage (bytes): K row of key 32 kb + n; V chunk read by this lane
+    // in the transposing load (lane 16 G + s: key offset s / 4, 8-byte piece s % 4 of d-half G % 2)
+    const int koff = (n & 15) * KGRP + (n >> 4) * 256 + 16 * hf;
+    const int ls = lane & 15, lg = lane >> 4;
+    const int voff = (4 * hf + (ls >> 2)) * VGRP + 32 * (lg & 1) + 8 * (ls & 3);
 
     for (int t = 0; t < nT; ++t) {
         if (t + 1 < nT) {
-            tile_load(keys);
+            tile_load(keys, (t + 1) & 1);
             if (t + 2 < nT) tile_keys(t + 2, keys);
         }
-        const unsigned short* Ks = smem + (t & 1) * BUF;
-        const unsigned short* Vt = Ks + KELEMS;
+        const char* Kb = smem_b + (t & 1) * BUFB + koff;
+        const char* Vb = smem_b + (t & 1) * BUFB + KBYTES + voff;
 
         // S^T = K Q^T : s[kb], 32 keys x 32 rows each.  Masks (tiles that touch a region
         // boundary, the diagonal or a list tail) enter as the initial accumulator: 0 for a
@@ -230,7 +228,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         if (mode == 0) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 kf = *(const bf16x8*)(Ks + (32 * kb + n) * KSTR + 8 * hf);
+                const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb);
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0], kZero16, 0, 0, 0);
             }
         } else {
@@ -248,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
                     const bool ok = (jl <= jr) & ((jl < jn) | (jl >= jw));
                     bias[v] = ok ? 0.f : -INFINITY;
                 }
-                const bf16x8 kf = *(const bf16x8*)(Ks + (32 * kb + n) * KSTR + 8 * hf);
+                const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb);
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0], bias, 0, 0, 0);
             }
         }
@@ -256,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         for (int ks = 1; ks < 8; ++ks)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 kf = *(const bf16x8*)(Ks + (32 * kb + n) * KSTR + 16 * ks + 8 * hf);
+                const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb + 32 * ks);
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
             }
 
@@ -298,11 +296,17 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         for (int sg = 0; sg < 4; ++sg)
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                const bf16x8 vf = *(const bf16x8*)(Vt + vt_row(32 * db + n) + 16 * sg + 8 * hf);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sg >> 1][sg & 1], o[db], 0, 0, 0);
+                // keys 16 sg + 8 rd + 4 hf + (0..3) live in groups 8 rd + 4 hf + (0..3), row sg
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4*)(Vb + sg * 256 + 64 * db));
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4*)(Vb + 8 * VGRP + sg * 256 + 64 * db));
+                const shortx8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf[sg >> 1][sg & 1],
+                                                                 o[db], 0, 0, 0);
             }
 
-        if (t + 1 < nT) tile_store((t + 1) & 1);
+        wait_vmem();                                 // next tile has landed in LDS
         __syncthreads();
     }
 
@@ -352,6 +356,6 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     }
 }
 
-size_t engine_bf16_lds_bytes() { return 2 * BUF * sizeof(unsigned short); }
+size_t engine_bf16_lds_bytes() { return 2 * BUFB; }
 
 }  // namespace aa
