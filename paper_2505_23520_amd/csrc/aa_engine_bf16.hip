@@ -79,6 +79,10 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     const Seq sq = seq_of(p, wk.b);
     const int row0 = wk.i * BQ;
     if (row0 >= sq.len) return;
+    // The two waves that share a SIMD (one from each resident work-group) sit in wave slots 0 and 1
+    // (HW_ID bits 3:0).  The odd slot gets the higher issue priority, so the pair does not settle
+    // into lockstep (both in their MFMA phase, then both in their softmax phase) but interleaves.
+    if (__builtin_amdgcn_s_getreg(0x1804) & 1) __builtin_amdgcn_s_setprio(2);
     const int hk = wk.h / p.grp;
     const int g = wk.i / p.step;
     const int rw = row0 + 32 * wave;                 // first row of this wave
