@@ -43,7 +43,7 @@ constexpr int KGRP = 1024 + 16;      // bytes per K group: 4 rows + pad
 constexpr int VGRP = 1024 + 64;      // bytes per V group
 constexpr int KBYTES = 16 * KGRP;
 constexpr int VBYTES = 16 * VGRP;
-constexpr int BUFB = KBYTES + VBYTES; // one stage, bytes
+constexpr int LDSB = 2 * KBYTES + 2 * VBYTES;  // two K stages, then two V stages
 constexpr float kRescaleLog2 = 8.f;  // raise the reference only for jumps above 2^8
 constexpr floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
@@ -139,17 +139,20 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             key[0] = x.x; key[1] = x.y; key[2] = x.z; key[3] = x.w;
         }
     };
-    auto tile_load = [&](const int* key, int buf) {  // asynchronous: completion is awaited by wait_vmem()
-        char* Kb = smem_b + buf * BUFB;
-        char* Vb = Kb + KBYTES;
+    // asynchronous direct-to-LDS loads of one tile's K (or V) rows; completion is awaited by wait_vmem()
+    auto load_k = [&](const int* key, int buf) {
+        char* Kb = smem_b + buf * KBYTES;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int gi = 4 * wave + j;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(Kb + gi * KGRP), 16,
+        for (int j = 0; j < 4; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(Kb + (4 * wave + j) * KGRP), 16,
                                                      (int)((unsigned)key[j] * kstb + 16u * lch), 0, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(vrs, (lds_void*)(Vb + gi * VGRP), 16,
+    };
+    auto load_v = [&](const int* key, int buf) {
+        char* Vb = smem_b + 2 * KBYTES + buf * VBYTES;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(vrs, (lds_void*)(Vb + (4 * wave + j) * VGRP), 16,
                                                      (int)((unsigned)key[j] * vstb + 16u * lch), 0, 0, 0);
-        }
     };
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane (n, hf) holds Q[row][16 ks + 8 hf .. +8)
@@ -193,34 +196,17 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
     }
 
-    // ---- pipeline prologue
-    int keys[4];
-    if (nT > 0) {
-        tile_keys(0, keys);
-        tile_load(keys, 0);
-        if (nT > 1) tile_keys(1, keys);
-    }
-    wait_vmem();
-    __syncthreads();
-
     // operand addresses inside a stage (bytes): K row of key 32 kb + n; V chunk read by this lane
     // in the transposing load (lane 16 G + s: key offset s / 4, 8-byte piece s % 4 of d-half G % 2)
     const int koff = (n & 15) * KGRP + (n >> 4) * 256 + 16 * hf;
     const int ls = lane & 15, lg = lane >> 4;
     const int voff = (4 * hf + (ls >> 2)) * VGRP + 32 * (lg & 1) + 8 * (ls & 3);
 
-    for (int t = 0; t < nT; ++t) {
-        if (t + 1 < nT) {
-            tile_load(keys, (t + 1) & 1);
-            if (t + 2 < nT) tile_keys(t + 2, keys);
-        }
-        const char* Kb = smem_b + (t & 1) * BUFB + koff;
-        const char* Vb = smem_b + (t & 1) * BUFB + KBYTES + voff;
-
-        // S^T = K Q^T : s[kb], 32 keys x 32 rows each.  Masks (tiles that touch a region
-        // boundary, the diagonal or a list tail) enter as the initial accumulator: 0 for a
-        // visible (key, row) pair, -inf otherwise; the common unmasked tile starts from literal 0.
-        floatx16 s[2];
+    // S^T = K Q^T of tile t: s[kb], 32 keys x 32 rows each.  Masks (tiles that touch a region
+    // boundary, the diagonal or a list tail) enter as the initial accumulator: 0 for a visible
+    // (key, row) pair, -inf otherwise; the common unmasked tile starts from literal 0.
+    auto scores = [&](int t, floatx16* s) {
+        const char* Kb = smem_b + (t & 1) * KBYTES + koff;
         int mode = 0, t0 = 0;
         if (t < nA) {
             t0 = tile_start(t);
@@ -261,6 +247,35 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
                 const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb + 32 * ks);
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
             }
+    };
+
+    // ---- software pipeline.  In iteration t the MFMAs of tile t+1's scores are issued next to the
+    // softmax arithmetic of tile t, then tile t's P V follows; K of tile t+2 and V of tile t+1
+    // stream into the LDS stages that tiles t and t-1 have released.  kA / kB hold this lane's
+    // source rows of tiles t+1 / t+2.
+    int kA[4] = {0, 0, 0, 0}, kB[4] = {0, 0, 0, 0};
+    floatx16 sA[2], sB[2];
+    if (nT > 0) {
+        tile_keys(0, kA);
+        load_k(kA, 0);
+        load_v(kA, 0);
+        if (nT > 1) { tile_keys(1, kA); load_k(kA, 1); }
+        if (nT > 2) tile_keys(2, kB);
+    }
+    wait_vmem();
+    __syncthreads();
+    if (nT > 0) scores(0, sA);
+    __syncthreads();                                 // K stage 0 may be overwritten from here on
+
+    auto step = [&](int t, floatx16* s, floatx16* snext) {
+        if (t + 1 < nT) load_v(kA, (t + 1) & 1);
+        if (t + 2 < nT) load_k(kB, t & 1);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) kA[e] = kB[e];
+        if (t + 3 < nT) tile_keys(t + 3, kB);
+        // (after the last tile this recomputes the last tile's scores; they are not used)
+        scores(min(t + 1, nT - 1), snext);
+        const char* Vb = smem_b + 2 * KBYTES + (t & 1) * VBYTES + voff;
 
         // online softmax of this lane's query row (the other half of the row is 32 lanes away)
         float mx = fmaxf(s[0][0], s[1][0]);
@@ -268,6 +283,15 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s[0][v], s[1][v]));
         mx = fmaxf(mx, xhalf(mx));
         mtrue = fmaxf(mtrue, mx);
+        // issue order of the straight-line code above: the row-max arithmetic of this tile fills
+        // the issue slots between the MFMAs of the next tile's scores
+        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);       // LDS reads run 3 ahead
+#pragma unroll
+        for (int i = 0; i < 14; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // three VALU
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+        }
         if (__any(mx > mref + rescale_gap)) {                 // rare after the first tiles
             const float mnew = fmaxf(mref, mx);
             const float alpha = (mnew == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mnew) * c2);
@@ -310,8 +334,12 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
                                                                  o[db], 0, 0, 0);
             }
 
-        wait_vmem();                                 // next tile has landed in LDS
+        wait_vmem();                                 // the loads issued above have landed in LDS
         __syncthreads();
+    };
+    for (int t = 0; t < nT; t += 2) {
+        step(t, sA, sB);
+        if (t + 1 < nT) step(t + 1, sB, sA);
     }
 
     // ---- epilogue
@@ -360,6 +388,6 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     }
 }
 
-size_t engine_bf16_lds_bytes() { return 2 * BUFB; }
+size_t engine_bf16_lds_bytes() { return LDSB; }
 
 }  // namespace aa
