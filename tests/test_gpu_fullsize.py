@@ -1,0 +1,84 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times
+(same entry points, same parameters), on sampled (sequence, head, group) units that the
+oracle computes one by one.  Units are independent, so a sampled comparison is exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2505_23520_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_2505_23520_amd import api as _api
+    assert torch.cuda.is_available()
+    return _api
+
+
+def _cfg(api, wl, **kw):
+    d = dict(block=wl.block, n_init=wl.n_init, window=wl.window, step=wl.step, theta=wl.theta)
+    d.update(kw)
+    return api.Config(**d)
+
+
+def _run(api, wl, cfg, signal, samples, packed=None):
+    from parity_util import GpuRun, check_groups
+    seqs = [synth.make_sequence(wl, s, signal=signal) for s in range(wl.B)]
+    run = GpuRun(api, seqs, cfg, wl.dtype, packed=packed).stages()
+    assert int(run.buf["flag"]) == 0
+    worst = check_groups(run, samples)
+    out, lse, stats = run.fused()
+    assert torch.equal(out, run.out)
+    del seqs
+    return run, worst, stats
+
+
+@pytest.mark.parametrize("signal", ["literal", "logit"])
+def test_gqa_8k_all_groups_of_sampled_heads(api, signal):
+    wl = synth.workloads()["gqa_8k"]
+    samples = [(0, h, g) for h in (0, 5, 18, 31) for g in range(4)]
+    run, worst, stats = _run(api, wl, _cfg(api, wl), signal, samples)
+    if signal == "literal":     # unit planted magnitudes: practically every candidate passes
+        assert worst["selected"] > 0.99 * worst["candidates"]
+    else:
+        assert 0 < worst["selected"] < 0.2 * worst["candidates"]
+
+
+def test_gqa_8k_step1(api):
+    wl = synth.workloads()["gqa_8k"]
+    samples = [(0, h, g) for h in (3, 28) for g in (0, 1, 2, 17, 40, 63)]
+    _run(api, wl, _cfg(api, wl, step=1, theta=4.5), "logit", samples)
+
+
+def test_gqa_32k_theta_sweep(api):
+    wl = synth.workloads()["gqa_32k"]
+    prev = -1
+    for theta in wl.extra["theta_sweep"]:
+        samples = [(0, 9, 3), (0, 22, 15), (0, 0, 8)]
+        run, worst, stats = _run(api, wl, _cfg(api, wl, theta=theta), "logit", samples)
+        assert worst["selected"] >= prev          # selections are nested in theta
+        prev = worst["selected"]
+        del run
+        torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("signal", ["literal", "logit"])
+def test_gqa_128k_sampled(api, signal):
+    wl = synth.workloads()["gqa_128k"]
+    samples = [(0, 0, 0), (0, 7, 1), (0, 13, 20), (0, 26, 41), (0, 31, 63)]
+    run, worst, stats = _run(api, wl, _cfg(api, wl), signal, samples)
+    N, Hq = wl.seqlens[0], wl.Hq
+    assert 0 < stats[0] <= Hq * N * (N + 1) // 2
+    del run
+    torch.cuda.empty_cache()
+
+
+def test_varlen_mixed_packed(api):
+    wl = synth.workloads()["varlen_mixed"]
+    samples = [(0, 2, 7), (1, 11, 0), (1, 30, 23), (2, 17, 47), (3, 5, 63), (3, 31, 30)]
+    run, worst, stats = _run(api, wl, _cfg(api, wl), "literal", samples, packed=True)
+    assert worst["selected"] > 0.99 * worst["candidates"]   # no planted structure: nearly dense
+    del run
+    torch.cuda.empty_cache()
