@@ -182,7 +182,21 @@ def main():
                        c["groups"][-1], c["groups"][0], wl.block * args.step, wl.name, c["seconds"], c["pairs"]))
         log(json.dumps(cpu))
 
+    # a plain device copy of known size: the reference dispatch that scales the FETCH_SIZE /
+    # WRITE_SIZE counters of a rocprofv3 --pmc run of this same command
+    cal_src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     N, d = wl.seqlens[0], wl.d
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "engine_bf16_stage3_%s_%s_traffic.txt" % (wl.name, args.signal))
+    if os.path.exists(tpath):
+        for ln in open(tpath):
+            if ln.startswith("traffic_bytes_per_launch="):
+                traffic = float(ln.split("=")[1])
     s3 = main_res["stage_ms"]["sparse"] * 1e-3
     flops3 = 4.0 * d * main_res["stage3_list_pairs"]
     line = {
@@ -199,7 +213,7 @@ def main():
         "mfma_peak_frac_whole_path": main_res["effective_tflops"] * 1e12 / MFMA_BF16_PEAK,
         "roofline": {"kernel": "engine_bf16_kernel (stage 3, gathered sparse attention)", "bound": "mfma",
                      "achieved": flops3 / s3 / 1e12 if flops3 else 0.0, "peak": MFMA_BF16_PEAK / 1e12,
-                     "unit": "TFLOP/s", "frac": flops3 / s3 / MFMA_BF16_PEAK if flops3 else 0.0, "traffic": None},
+                     "unit": "TFLOP/s", "frac": flops3 / s3 / MFMA_BF16_PEAK if flops3 else 0.0, "traffic": traffic},
         "calibrated": calibrated,
         "cpu_baseline": cpu,
     }
