@@ -16,6 +16,7 @@ namespace aa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+constexpr floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
 namespace {
 __device__ __forceinline__ float bf16_to_f(unsigned short b) { return __uint_as_float((unsigned)b << 16); }
@@ -76,12 +77,18 @@ __global__ __launch_bounds__(128) void pool_q_fp32_kernel(SelectArgs a) {
 }
 
 // ------------------------------------------------------------------ mask, bf16 MFMA
-// grid (key chunks, row tiles, B*Hq), 256 threads = 4 waves: wave (wr, wc) owns pooled rows
-// 64 wr .. +64 of the row tile and keys 64 wc .. +64 of every 128-key tile of the chunk.
-// A row tile holds RT = 128 - 128 % step pooled rows, so no group straddles two tiles.
-constexpr int kMaskTileKeys = 128;
+// grid (key chunks, row tiles, B*Hq), 256 threads = 4 waves, two work-groups per CU.
+// A row tile holds RT = 128 - 128 % step pooled rows, so no group straddles two tiles; wave w owns
+// its rows 32 w .. 32 w + 31.  The chunk's keys pass through LDS in 64-key tiles (16-byte
+// direct-to-LDS loads, double-buffered, same padded group layout as the attention engine).
+// C[key][row] = K qbar^T: keys are the M dimension, pooled rows the N dimension, so one lane owns
+// one pooled row and collects the compare bits of its row in registers.
+constexpr int kMaskTileKeys = 64;
+constexpr int kKGrp = 1024 + 16;                         // bytes per group of four K rows + pad
+constexpr int kKTile = 16 * kKGrp;
+typedef __attribute__((address_space(3))) void lds_void;
 
-__global__ __launch_bounds__(256) void mask_bf16_kernel(SelectArgs a) {
+__global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     const KParams& p = a.p;
     const int b = blockIdx.z / p.Hq, h = blockIdx.z % p.Hq, hk = h / p.grp;
     const Seq sq = seq_of(p, b);
@@ -97,99 +104,105 @@ __global__ __launch_bounds__(256) void mask_bf16_kernel(SelectArgs a) {
     const int chunk0 = key_lo + blockIdx.x * a.keys_per_chunk;
     if (chunk0 >= Wmax) return;
     const int chunk1 = min(chunk0 + a.keys_per_chunk, ((Wmax + kMaskTileKeys - 1) / kMaskTileKeys) * kMaskTileKeys);
+    const int ntiles = (chunk1 - chunk0) / kMaskTileKeys;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave & 1, wc = wave >> 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hf = lane >> 5;
+    __shared__ __attribute__((aligned(16))) char ktile[2 * kKTile];
+    __shared__ unsigned rowword[2][128][2];
 
-    // B operand: pooled query rows (hi and lo parts); lane (n, hf) holds row n, columns 16 ks + 8 hf .. +8
-    bf16x8 bhi[2][8], blo[2][8];
-    float xb[2];                                          // pooled anchor of the lane's row; NaN = no such row
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const int lr = 64 * wr + 32 * rb + n;             // row inside the tile
-        const bool ok = lr < rows_here;
-        const long long bi = blk_index(p, sq, b, h, row_t0 + (ok ? lr : 0));
+    // B operand: this lane's pooled query row, hi and lo parts, columns 16 ks + 8 hf .. +8
+    bf16x8 bhi[8], blo[8];
+    const int lr = 32 * wave + n;                        // row inside the tile
+    const bool rok = lr < rows_here;
+    const long long bi = blk_index(p, sq, b, h, row_t0 + (rok ? lr : 0));
+    {
         const unsigned short* hi = (const unsigned short*)a.qp_hi + bi * 128;
         const unsigned short* lo = (const unsigned short*)a.qp_lo + bi * 128;
+        const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            uint4 x = *(const uint4*)(hi + 16 * ks + 8 * hf);
-            uint4 y = *(const uint4*)(lo + 16 * ks + 8 * hf);
-            if (!ok) { x = make_uint4(0, 0, 0, 0); y = x; }
-            bhi[rb][ks] = *(bf16x8*)&x;
-            blo[rb][ks] = *(bf16x8*)&y;
+            const bf16x8 x = *(const bf16x8*)(hi + 16 * ks + 8 * hf);
+            const bf16x8 y = *(const bf16x8*)(lo + 16 * ks + 8 * hf);
+            bhi[ks] = rok ? x : zero8;
+            blo[ks] = rok ? y : zero8;
         }
-        xb[rb] = ok ? (p.use_anchor ? a.xa[bi] : 0.f) : __builtin_nanf("");
     }
+    // pooled anchor of the lane's row; NaN = no such row (never selects)
+    const float xb = rok ? (p.use_anchor ? a.xa[bi] : 0.f) : __builtin_nanf("");
 
     const unsigned short* kbase = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, b, hk, 0);
-    const long long kst = p.ks[2];
-    __shared__ unsigned rowword[128][4];
+    const unsigned kstb = (unsigned)p.ks[2] * 2u;
+    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)kbase, 0, (int)((unsigned)(sq.len - 1) * kstb + 256u), 0x00020000);
+    // loader: in the load of group gi lane l fetches the 16-byte chunk l % 16 of key 16 (l / 16) + gi
+    auto load_tile = [&](int t0, int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gi = 4 * wave + j;
+            const int key = min(t0 + 16 * (lane >> 4) + gi, sq.len - 1);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(ktile + buf * kKTile + gi * kKGrp), 16,
+                                                     (int)((unsigned)key * kstb + 16u * (lane & 15)), 0, 0, 0);
+        }
+    };
     const int nwords = a.nwords;
     const int ngrp = (nblk + p.step - 1) / p.step;
-
-    for (int t0 = chunk0; t0 < chunk1; t0 += kMaskTileKeys) {
-        // C[key][row]: keys are the M dimension (A operand straight from global memory),
-        // pooled rows the N dimension, so one lane owns one pooled row
-        floatx16 c[2][2];                                 // [kb][rb]
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) c[kb][rb][v] = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            const int key = min(t0 + 64 * wc + 32 * kb + n, sq.len - 1);
-            const unsigned short* kr = kbase + (long long)key * kst + 8 * hf;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const uint4 x = *(const uint4*)(kr + 16 * ks);
-                const bf16x8 kf = *(const bf16x8*)&x;
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb) {
-                    c[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, blo[rb][ks], c[kb][rb], 0, 0, 0);
-                    c[kb][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, bhi[rb][ks], c[kb][rb], 0, 0, 0);
-                }
-            }
-        }
-        // threshold compare; the lane gathers the bits of its 16 keys per 32-key block, the
-        // other half of the wave holds the remaining 16
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                unsigned wd = 0;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const bool pred = (xb[rb] - p.sigma * c[kb][rb][v]) <= p.theta;
-                    wd |= pred ? (1u << (8 * (v >> 2) + (v & 3))) : 0u;
-                }
-                wd <<= 4 * hf;
-                wd |= (unsigned)__shfl_xor((int)wd, 32, 64);
-                if (hf == 0) rowword[64 * wr + 32 * rb + n][2 * wc + kb] = wd;
-            }
-        __syncthreads();
-        // OR the rows of each group, clip to the group's candidate range, write the bit words
-        const int ngt = g_last - g_first + 1;
-        for (int e = tid; e < ngt * 4; e += 256) {
-            const int gi = e >> 2, wi = e & 3;
+    const int ngt = g_last - g_first + 1;
+    // OR the rows of each group, clip to the group's candidate range, write the bit words of a tile
+    auto combine = [&](int t0, int par) {
+        for (int e = tid; e < ngt * 2; e += 256) {
+            const int gi = e >> 1, wi = e & 1;
             const int g = g_first + gi;
             const int lr0 = g * p.step - row_t0;
             unsigned wd = 0;
-            for (int s = 0; s < p.step && lr0 + s < rows_here; ++s) wd |= rowword[lr0 + s][wi];
+            for (int s = 0; s < p.step && lr0 + s < rows_here; ++s) wd |= rowword[par][lr0 + s][wi];
             const int j0 = t0 + 32 * wi;
             const int Wg = window_start(p, g);
-            // keep bits with n_init <= j0 + bit < Wg
-            const int lo = max(p.n_init - j0, 0), hi = min(Wg - j0, 32);
+            const int lo = max(p.n_init - j0, 0), hi = min(Wg - j0, 32);   // keep n_init <= j0 + bit < Wg
             unsigned keep = 0;
             if (hi > lo) keep = (hi - lo >= 32) ? 0xffffffffu : (((1u << (hi - lo)) - 1u) << lo);
             if (g < ngrp && j0 / 32 < nwords)
                 a.bits[grp_index(p, sq, b, h, g) * nwords + j0 / 32] = wd & keep;
         }
+    };
+
+    load_tile(chunk0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
+    __syncthreads();
+    const int koff = (n & 15) * kKGrp + (n >> 4) * 256 + 16 * hf;   // K row of key 32 kb + n
+    for (int t = 0; t < ntiles; ++t) {
+        const int t0 = chunk0 + t * kMaskTileKeys;
+        if (t + 1 < ntiles) load_tile(t0 + kMaskTileKeys, (t + 1) & 1);
+        const char* Kb = ktile + (t & 1) * kKTile + koff;
+        floatx16 c[2];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb + 32 * ks);
+                c[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, blo[ks], ks == 0 ? kZero16 : c[kb], 0, 0, 0);
+                c[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, bhi[ks], c[kb], 0, 0, 0);
+            }
+        // threshold compare; the lane gathers the bits of its 16 keys per 32-key block, the
+        // other half of the wave holds the remaining 16
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            unsigned wd = 0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const bool pred = (xb - p.sigma * c[kb][v]) <= p.theta;
+                wd |= pred ? (1u << (8 * (v >> 2) + (v & 3))) : 0u;
+            }
+            wd <<= 4 * hf;
+            wd |= (unsigned)__shfl_xor((int)wd, 32, 64);
+            if (hf == 0) rowword[t & 1][lr][kb] = wd;
+        }
+        if (t > 0) combine(t0 - kMaskTileKeys, (t - 1) & 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // next tile has landed
         __syncthreads();
     }
+    combine(chunk0 + (ntiles - 1) * kMaskTileKeys, (ntiles - 1) & 1);
 }
 
 // ------------------------------------------------------------------ mask, fp32 vector FMA
