@@ -28,7 +28,9 @@
  * -------
  *  q, out: element (b, h, r, c) at  b*stride[0] + h*stride[1] + r*stride[2] + c
  *  k, v  : same with KV heads.  The last dimension (d) is contiguous.  Strides
- *  are in ELEMENTS.  dtype AA_BF16: 2-byte bfloat16, AA_FP32: 4-byte float.
+ *  are in ELEMENTS, multiples of 16 bytes; pointers are 16-byte aligned.  bf16:
+ *  one head's K (and V) rows must span less than 2 GiB (N * stride[2] * 2 < 2^31).
+ *  dtype AA_BF16: 2-byte bfloat16, AA_FP32: 4-byte float.
  *  Packed variable-length batches (cu_seqlens != NULL): sequence b holds tokens
  *  cu_seqlens[b] .. cu_seqlens[b+1]-1 of a packed token axis; stride[0] is
  *  ignored, r is replaced by cu_seqlens[b] + r, N is the longest sequence and
@@ -45,9 +47,9 @@
  *      packed      : t = h*grp_cap + (sum_{b'<b} ngrp(b')) + g, grp_cap from anchor_sizes()
  *  Selected columns: group t owns idx[offsets[t] .. offsets[t] + counts[t]),
  *  strictly ascending key positions inside the sequence.  offsets[t] is a
- *  multiple of 64 and the slots up to the next multiple of 64 after the list
- *  repeat the list's last entry (key n_init when the list is empty), so a reader
- *  may always fetch whole 64-entry chunks.
+ *  multiple of 64 and the slots up to the next multiple of 64 after a non-empty
+ *  list repeat its last entry, so a reader may always fetch whole 64-entry
+ *  chunks (an empty list owns no slots).
  */
 #ifndef ANCHOR_ATTENTION_H
 #define ANCHOR_ATTENTION_H
@@ -72,7 +74,7 @@ enum {
 typedef struct aa_params {
     int32_t B, Hq, Hkv;       /* batch (sequences), query heads, KV heads (Hq % Hkv == 0)      */
     int32_t N;                /* sequence length; longest sequence when cu_seqlens != NULL     */
-    int32_t d;                /* head dimension: bf16 -> 128; fp32 -> multiple of 4, <= 128     */
+    int32_t d;                /* head dimension: bf16 -> 128; fp32 -> 32, 64 or 128             */
     int32_t block_q;          /* b_q : bf16 -> 128; fp32 -> 16..128, multiple of 16             */
     int32_t block_kv;         /* b_kv: tile size of the paper's listings; must equal block_q    */
     int32_t n_init;           /* initial tokens always attended (paper: one KV block), >= 0     */

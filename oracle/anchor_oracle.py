@@ -101,11 +101,14 @@ def n_groups(N: int, p: OracleParams) -> int:
     return (N + span - 1) // span
 
 
-def run_group(q, k, v, p: OracleParams, g: int, want_acc: bool = False, attend: bool = True):
+def run_group(q, k, v, p: OracleParams, g: int, want_acc: bool = False, attend: bool = True,
+              zero_anchor: bool = False):
     """Whole pipeline for group ``g`` of one head.  q,k,v: float32 [N,d], C order.
 
     Returns a dict: rows (r0,r1), M, L, (Acc), xbar[nb], qbar[nb,d], sel (uint8[N]),
     margin (float64[N]), idx (ascending int64), O, lse, pairs.
+    zero_anchor: selection compares against an anchor of zero (the "Without Anchor" rows of
+    Table 4); M, L, Acc and xbar are still the true anchor state.
     """
     lib = _load()
     q = np.ascontiguousarray(q, dtype=np.float32)
@@ -131,7 +134,8 @@ def run_group(q, k, v, p: OracleParams, g: int, want_acc: bool = False, attend: 
         xbar[b] = xb.value
     sel = np.empty(N, np.uint8)
     margin = np.empty(N, np.float64)
-    cnt = lib.ao_select_group(cp, _ptr(k), g, nb, _ptr(xbar), _ptr(qbar), _ptr(sel), _ptr(margin))
+    xsel = np.zeros_like(xbar) if zero_anchor else xbar
+    cnt = lib.ao_select_group(cp, _ptr(k), g, nb, _ptr(xsel), _ptr(qbar), _ptr(sel), _ptr(margin))
     idx = np.nonzero(sel)[0].astype(np.int64)
     assert cnt == idx.size
     out = dict(rows=(r0, r1), M=M, L=L, Acc=Acc, xbar=xbar, qbar=qbar, sel=sel, margin=margin,

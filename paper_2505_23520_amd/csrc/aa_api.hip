@@ -70,6 +70,9 @@ int make_plan(const aa_params* p, Plan* pl) {
     const int vec = p->dtype == AA_BF16 ? 8 : 4;             // elements per 16-byte access
     if (p->dtype == AA_BF16) {
         if (p->d != 128 || p->block_q != 128) return AA_EUNSUPPORTED;
+        // K / V rows are addressed with 32-bit byte offsets from the head's first row
+        if ((int64_t)p->N * p->k_stride[2] * 2 >= (1ll << 31) || (int64_t)p->N * p->v_stride[2] * 2 >= (1ll << 31))
+            return AA_EUNSUPPORTED;
     } else {
         if (p->d != 32 && p->d != 64 && p->d != 128) return AA_EUNSUPPORTED;
         if (p->block_q < 16 || p->block_q > 128 || p->block_q % 16) return AA_EUNSUPPORTED;

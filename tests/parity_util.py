@@ -134,7 +134,7 @@ def check_groups(run: GpuRun, samples, check_state=True, out=None, lse=None):
         s = run.seqs[b]
         q, k, v = s["q"][h], s["k"][h // grp], s["v"][h // grp]
         N = q.shape[0]
-        ref = ao.run_group(q, k, v, op, g, want_acc=check_state, attend=False)
+        ref = ao.run_group(q, k, v, op, g, want_acc=check_state, attend=False, zero_anchor=not cfg.use_anchor)
         r0, r1 = ref["rows"]
         ri0 = run.row_index(b, h, r0)
         if check_state:

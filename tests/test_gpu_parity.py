@@ -157,6 +157,15 @@ def test_bf16_recompute_anchor_in_stage3(api):
     assert (lse2 - B["lse"]).abs().max().item() <= 1e-4
 
 
+@pytest.mark.parametrize("dtype,d,block", [("bf16", 128, 128), ("fp32", 64, 64)])
+def test_without_anchor_variant(api, dtype, d, block):
+    """use_anchor = 0: the pooled scores are compared against a zero anchor (Table 4, "Without Anchor")."""
+    wl = _wl("t", dtype, [1536], 2, 1, d, block, 75, 24)
+    cfg = api.Config(block=block, n_init=block, window=block, step=2, theta=-1.5, use_anchor=False)
+    run, worst = _run_and_check(api, wl, cfg)
+    assert 0 < worst["selected"] < worst["candidates"]
+
+
 def test_packed_varlen(api):
     for dtype, d, block, lens in (("bf16", 128, 128, [300, 1024, 129, 2000]), ("fp32", 64, 32, [100, 333, 64])):
         wl = _wl("t", dtype, lens, 4, 2, d, block, 80, 12)

@@ -248,3 +248,25 @@ def test_invariants_nested_rowsum_recall():
         assert np.all(res["lse"] >= res["M"] + np.log(res["L"]) - 1e-12)  # stage 3 only adds keys
         prev_sets, prev_recall, prev_pairs = sets, recall.mean(), res["pairs"]
     assert prev_pairs == N * (N + 1) // 2 and abs(prev_recall - 1.0) < 1e-12
+
+
+def test_zero_anchor_variant_selects_on_pooled_score_alone():
+    """Table 4's "Without Anchor" rows set the anchor to zero: column j is kept iff
+    -sigma * <qbar_i, k_j> <= theta for some block of the group."""
+    N, d, bq, ninit, w, step, theta = 192, 8, 16, 4, 16, 2, -0.3
+    q, k, v = _rand(N, d, 5)
+    p = ao.OracleParams(bq, ninit, w, step, theta)
+    sigma = 1.0 / math.sqrt(d)
+    for g in range(ao.n_groups(N, p)):
+        res = ao.run_group(q, k, v, p, g, attend=False, zero_anchor=True)
+        want = np.zeros(N, bool)
+        for b in range(step):
+            i = g * step + b
+            if i * bq >= N:
+                break
+            qbar = q[i * bq:(i + 1) * bq].astype(np.float64).mean(0)
+            s = sigma * (k.astype(np.float64) @ qbar)
+            want |= (-s <= theta)
+        want[:ninit] = False
+        want[res["W"]:] = False
+        np.testing.assert_array_equal(res["sel"].astype(bool), want)
