@@ -15,7 +15,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libanchor_attention.so")
+LIB_PATH = os.environ.get("ANCHOR_ATTENTION_LIB", os.path.join(_HERE, "libanchor_attention.so"))
 
 AA_FP32, AA_BF16 = 0, 1
 AA_OK, AA_EINVAL, AA_EUNSUPPORTED, AA_EWORKSPACE, AA_EHIP = 0, -1, -2, -3, -4
