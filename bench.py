@@ -182,13 +182,30 @@ def main():
                        c["groups"][-1], c["groups"][0], wl.block * args.step, wl.name, c["seconds"], c["pairs"]))
         log(json.dumps(cpu))
 
-    # a plain device copy of known size: the reference dispatch that scales the FETCH_SIZE /
-    # WRITE_SIZE counters of a rocprofv3 --pmc run of this same command
-    cal_src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
-    cal_dst = torch.empty_like(cal_src)
-    cal_dst.copy_(cal_src)
+    # rates this GPU sustains at its actual clock: register-only MFMA loop, 1 GiB device copies
+    # (the copies are also the dispatches of known size that scale the FETCH_SIZE / WRITE_SIZE
+    # counters of a rocprofv3 --pmc run of this same command)
+    scratch = torch.empty(1 << 18, dtype=torch.float32, device="cuda")
+    api.anchor_probe_mfma(200, scratch)
     torch.cuda.synchronize()
-    del cal_src, cal_dst
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record()
+    flop = api.anchor_probe_mfma(10000, scratch)
+    p1.record()
+    torch.cuda.synchronize()
+    mfma_sustained = flop / (p0.elapsed_time(p1) * 1e-3)
+    cp_src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    torch.cuda.synchronize()
+    p0.record()
+    for _ in range(4):
+        cp_dst.copy_(cp_src)
+    p1.record()
+    torch.cuda.synchronize()
+    hbm_sustained = 4 * 2 * cp_src.numel() * 4 / (p0.elapsed_time(p1) * 1e-3)
+    del cp_src, cp_dst
+    log("sustained: MFMA %.0f TFLOP/s, copy %.2f TB/s" % (mfma_sustained / 1e12, hbm_sustained / 1e12))
 
     N, d = wl.seqlens[0], wl.d
     traffic = None
@@ -213,7 +230,12 @@ def main():
         "mfma_peak_frac_whole_path": main_res["effective_tflops"] * 1e12 / MFMA_BF16_PEAK,
         "roofline": {"kernel": "engine_bf16_kernel (stage 3, gathered sparse attention)", "bound": "mfma",
                      "achieved": flops3 / s3 / 1e12 if flops3 else 0.0, "peak": MFMA_BF16_PEAK / 1e12,
-                     "unit": "TFLOP/s", "frac": flops3 / s3 / MFMA_BF16_PEAK if flops3 else 0.0, "traffic": traffic},
+                     "unit": "TFLOP/s", "frac": flops3 / s3 / MFMA_BF16_PEAK if flops3 else 0.0, "traffic": traffic,
+                     "hbm_achieved_GBps": (traffic / s3 / 1e9) if traffic else None,
+                     "hbm_frac_of_peak": (traffic / s3 / HBM_PEAK) if traffic else None,
+                     "sustained_mfma_TFLOPs_this_gpu": mfma_sustained / 1e12,
+                     "frac_of_sustained_mfma": flops3 / s3 / mfma_sustained if flops3 else 0.0,
+                     "sustained_copy_TBps_this_gpu": hbm_sustained / 1e12},
         "calibrated": calibrated,
         "cpu_baseline": cpu,
     }

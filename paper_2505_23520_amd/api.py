@@ -65,13 +65,15 @@ _lib.anchor_attention_prefill.restype = ctypes.c_int
 _lib.anchor_attention_prefill.argtypes = [_PP, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, _P]
 _lib.dense_causal_flash.restype = ctypes.c_int
 _lib.dense_causal_flash.argtypes = [_PP, _P, _P, _P, _P, _P, _P]
+_lib.anchor_probe_mfma.restype = ctypes.c_int
+_lib.anchor_probe_mfma.argtypes = [ctypes.c_int, _P, _P]
 _lib.anchor_strerror.restype = ctypes.c_char_p
 _lib.anchor_strerror.argtypes = [ctypes.c_int]
 _lib.anchor_last_hip_error.restype = ctypes.c_char_p
 _lib.anchor_last_hip_error.argtypes = []
 
 EXPORTS = ("anchor_sizes", "anchor_compute", "stripe_select", "sparse_attn", "anchor_attention_prefill",
-           "dense_causal_flash", "anchor_strerror", "anchor_last_hip_error")
+           "dense_causal_flash", "anchor_probe_mfma", "anchor_strerror", "anchor_last_hip_error")
 
 
 class AnchorError(RuntimeError):
@@ -178,6 +180,12 @@ def anchor_attention_prefill(p, q, k, v, out, lse, stats, ws, stream=None):
 def dense_causal_flash(p, q, k, v, out, lse=None, stream=None):
     _check(_lib.dense_causal_flash(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
                                    _stream(stream)))
+
+
+def anchor_probe_mfma(iters, scratch, stream=None):
+    """Enqueue the register-only MFMA loop; returns the FLOP it performs."""
+    _check(_lib.anchor_probe_mfma(int(iters), _ptr(scratch), _stream(stream)))
+    return 1024 * 4 * int(iters) * 16 * 32768.0
 
 
 def alloc_stage_buffers(p: aa_params, device="cuda", want_acc=True, idx_capacity=None) -> dict:
