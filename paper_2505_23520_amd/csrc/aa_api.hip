@@ -161,14 +161,7 @@ int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
     const KParams& k = pl.kp;
     const unsigned grid = (unsigned)((long long)k.nblk_max * k.Hq * k.B);
     if (dtype == AA_BF16) {
-        static bool attr_set = false;
-        const size_t lds = engine_bf16_lds_bytes();
-        if (!attr_set) {
-            AA_HIP(hipFuncSetAttribute((const void*)engine_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds));
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(256), lds, st, ea);
+        hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(256), 0, st, ea);
         AA_LAUNCHED("engine_bf16_kernel");
     } else {
         const size_t lds = engine_fp32_lds_bytes(k.d, k.bq);

@@ -27,7 +27,6 @@ struct EngineArgs {
 };
 
 __global__ void engine_bf16_kernel(EngineArgs a);
-size_t engine_bf16_lds_bytes();
 
 __global__ void engine_fp32_kernel(EngineArgs a);
 size_t engine_fp32_lds_bytes(int d, int bq);

@@ -43,7 +43,7 @@ constexpr int KGRP = 1024 + 16;      // bytes per K group: 4 rows + pad
 constexpr int VGRP = 1024 + 64;      // bytes per V group
 constexpr int KBYTES = 16 * KGRP;
 constexpr int VBYTES = 16 * VGRP;
-constexpr int LDSB = 2 * KBYTES + 2 * VBYTES;  // two K stages, then two V stages
+constexpr int BUFB = KBYTES + VBYTES; // one stage, bytes
 constexpr float kRescaleLog2 = 8.f;  // raise the reference only for jumps above 2^8
 constexpr floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
@@ -53,6 +53,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
 
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef short shortx8 __attribute__((ext_vector_type(8)));
@@ -68,7 +69,11 @@ __device__ __forceinline__ float xhalf(float x) {  // value held by the lane 32 
 }  // namespace
 
 __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
-    extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+    constexpr int NW = 4;                            // waves per work-group
+    // one LDS object per stage, so that the compiler can tell that the asynchronous loads into
+    // one stage do not alias the operand reads from the other
+    __shared__ __attribute__((aligned(16))) char Ks0[KBYTES], Ks1[KBYTES], Vs0[VBYTES], Vs1[VBYTES];
+    __shared__ float red[NW];
     const KParams& p = a.p;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -119,12 +124,12 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
         (void*)vb_, 0, (int)((unsigned)(sq.len - 1) * vstb + 2u * D), 0x00020000);
 
-    // ---- loader role of this wave: groups 4 wave .. 4 wave + 3 of every tile.  In the load of
-    // group gi lane l fetches the 16-byte chunk l % 16 of key 16 (l / 16) + gi of the tile, so each
-    // lane deals with the 4 consecutive keys 16 (l / 16) + 4 wave + j.
+    // ---- loader role of this wave: GPW = 16 / NW groups of every tile.  In the load of group gi
+    // lane l fetches the 16-byte chunk l % 16 of key 16 (l / 16) + gi of the tile, so each lane deals
+    // with the GPW consecutive keys 16 (l / 16) + GPW wave + j.
+    constexpr int GPW = 16 / NW;
     const int lch = lane & 15;
-    const int kq0 = 16 * (lane >> 4) + 4 * wave;     // first of this lane's 4 keys inside the tile
-    char* const smem_b = (char*)smem;
+    const int kq0 = 16 * (lane >> 4) + GPW * wave;   // first of this lane's keys inside the tile
 
     auto tile_start = [&](int t) -> int {            // first key of contiguous tile t (t < nA)
         return TK * (t < T1 ? t : t2s + (t - T1));
@@ -133,26 +138,28 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         if (t < nA) {
             const int t0 = tile_start(t) + kq0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) key[e] = min(t0 + e, sq.len - 1);
+            for (int e = 0; e < GPW; ++e) key[e] = min(t0 + e, sq.len - 1);
         } else {
-            const intx4 x = *(const intx4*)(a.idx + lbase + (long long)(t - nA) * TK + kq0);
-            key[0] = x.x; key[1] = x.y; key[2] = x.z; key[3] = x.w;
+            const int* src = a.idx + lbase + (long long)(t - nA) * TK + kq0;
+            if constexpr (GPW == 4) {
+                const intx4 x = *(const intx4*)src;
+                key[0] = x.x; key[1] = x.y; key[2] = x.z; key[3] = x.w;
+            } else {
+                const intx2 x = *(const intx2*)src;
+                key[0] = x.x; key[1] = x.y;
+            }
         }
     };
-    // asynchronous direct-to-LDS loads of one tile's K (or V) rows; completion is awaited by wait_vmem()
-    auto load_k = [&](const int* key, int buf) {
-        char* Kb = smem_b + buf * KBYTES;
+    // asynchronous: completion is awaited by wait_vmem()
+    auto tile_load = [&](const int* key, char* Kb, char* Vb) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(Kb + (4 * wave + j) * KGRP), 16,
+        for (int j = 0; j < GPW; ++j) {
+            const int gi = GPW * wave + j;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(Kb + gi * KGRP), 16,
                                                      (int)((unsigned)key[j] * kstb + 16u * lch), 0, 0, 0);
-    };
-    auto load_v = [&](const int* key, int buf) {
-        char* Vb = smem_b + 2 * KBYTES + buf * VBYTES;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(vrs, (lds_void*)(Vb + (4 * wave + j) * VGRP), 16,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(vrs, (lds_void*)(Vb + gi * VGRP), 16,
                                                      (int)((unsigned)key[j] * vstb + 16u * lch), 0, 0, 0);
+        }
     };
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane (n, hf) holds Q[row][16 ks + 8 hf .. +8)
@@ -196,17 +203,33 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
     }
 
+    // ---- pipeline prologue
+    int keys[GPW];
+    if (nT > 0) {
+        tile_keys(0, keys);
+        tile_load(keys, Ks0, Vs0);
+        if (nT > 1) tile_keys(1, keys);
+    }
+    wait_vmem();
+    __syncthreads();
+
     // operand addresses inside a stage (bytes): K row of key 32 kb + n; V chunk read by this lane
     // in the transposing load (lane 16 G + s: key offset s / 4, 8-byte piece s % 4 of d-half G % 2)
     const int koff = (n & 15) * KGRP + (n >> 4) * 256 + 16 * hf;
     const int ls = lane & 15, lg = lane >> 4;
     const int voff = (4 * hf + (ls >> 2)) * VGRP + 32 * (lg & 1) + 8 * (ls & 3);
 
-    // S^T = K Q^T of tile t: s[kb], 32 keys x 32 rows each.  Masks (tiles that touch a region
-    // boundary, the diagonal or a list tail) enter as the initial accumulator: 0 for a visible
-    // (key, row) pair, -inf otherwise; the common unmasked tile starts from literal 0.
-    auto scores = [&](int t, floatx16* s) {
-        const char* Kb = smem_b + (t & 1) * KBYTES + koff;
+    auto tile_step = [&](int t, const char* Kcur, const char* Vcur, char* Knext, char* Vnext) {
+        if (t + 1 < nT) {
+            tile_load(keys, Knext, Vnext);
+            if (t + 2 < nT) tile_keys(t + 2, keys);
+        }
+        const char* Kb = Kcur + koff;
+        const char* Vb = Vcur + voff;
+
+        // S^T = K Q^T : s[kb], 32 keys x 32 rows each.  Masks (tiles that touch a region
+        // boundary, the diagonal or a list tail) enter as the initial accumulator: 0 for a
+        // visible (key, row) pair, -inf otherwise; the common unmasked tile starts from literal 0.
         int mode = 0, t0 = 0;
         if (t < nA) {
             t0 = tile_start(t);
@@ -215,6 +238,10 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         } else if (t == nT - 1 && (cnt & (TK - 1))) {
             mode = 2;
         }
+        // a contiguous tile that starts beyond this wave's last row is hidden from all its rows
+        // (the work-group still needs it for its later rows): nothing to compute
+        if (!(t < nA && t0 > rw + 31)) {
+        floatx16 s[2];
         if (mode == 0) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -247,35 +274,13 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
                 const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb + 32 * ks);
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
             }
-    };
-
-    // ---- software pipeline.  In iteration t the MFMAs of tile t+1's scores are issued next to the
-    // softmax arithmetic of tile t, then tile t's P V follows; K of tile t+2 and V of tile t+1
-    // stream into the LDS stages that tiles t and t-1 have released.  kA / kB hold this lane's
-    // source rows of tiles t+1 / t+2.
-    int kA[4] = {0, 0, 0, 0}, kB[4] = {0, 0, 0, 0};
-    floatx16 sA[2], sB[2];
-    if (nT > 0) {
-        tile_keys(0, kA);
-        load_k(kA, 0);
-        load_v(kA, 0);
-        if (nT > 1) { tile_keys(1, kA); load_k(kA, 1); }
-        if (nT > 2) tile_keys(2, kB);
-    }
-    wait_vmem();
-    __syncthreads();
-    if (nT > 0) scores(0, sA);
-    __syncthreads();                                 // K stage 0 may be overwritten from here on
-
-    auto step = [&](int t, floatx16* s, floatx16* snext) {
-        if (t + 1 < nT) load_v(kA, (t + 1) & 1);
-        if (t + 2 < nT) load_k(kB, t & 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) kA[e] = kB[e];
-        if (t + 3 < nT) tile_keys(t + 3, kB);
-        // (after the last tile this recomputes the last tile's scores; they are not used)
-        scores(min(t + 1, nT - 1), snext);
-        const char* Vb = smem_b + 2 * KBYTES + (t & 1) * VBYTES + voff;
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
 
         // online softmax of this lane's query row (the other half of the row is 32 lanes away)
         float mx = fmaxf(s[0][0], s[1][0]);
@@ -283,15 +288,6 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s[0][v], s[1][v]));
         mx = fmaxf(mx, xhalf(mx));
         mtrue = fmaxf(mtrue, mx);
-        // issue order of the straight-line code above: the row-max arithmetic of this tile fills
-        // the issue slots between the MFMAs of the next tile's scores
-        __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);       // LDS reads run 3 ahead
-#pragma unroll
-        for (int i = 0; i < 14; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // three VALU
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-        }
         if (__any(mx > mref + rescale_gap)) {                 // rare after the first tiles
             const float mnew = fmaxf(mref, mx);
             const float alpha = (mnew == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mnew) * c2);
@@ -334,12 +330,13 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
                                                                  o[db], 0, 0, 0);
             }
 
-        wait_vmem();                                 // the loads issued above have landed in LDS
+        }
+        wait_vmem();                                 // next tile has landed in LDS
         __syncthreads();
     };
     for (int t = 0; t < nT; t += 2) {
-        step(t, sA, sB);
-        if (t + 1 < nT) step(t + 1, sB, sA);
+        tile_step(t, Ks0, Vs0, Ks1, Vs1);
+        if (t + 1 < nT) tile_step(t + 1, Ks1, Vs1, Ks0, Vs0);
     }
 
     // ---- epilogue
@@ -364,7 +361,6 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             float red_m = (rok && hf == 0) ? ms : 0.f;
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) red_m += __shfl_xor(red_m, off, 64);
-            float* red = (float*)smem;               // all tile reads are behind the last barrier
             if (lane == 0) red[wave] = red_m;
             __syncthreads();
             if (tid == 0) {
@@ -388,6 +384,5 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     }
 }
 
-size_t engine_bf16_lds_bytes() { return LDSB; }
 
 }  // namespace aa
