@@ -210,7 +210,7 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
         AA_LAUNCHED("zero_i32_kernel");
     }
     if (p->dtype == AA_BF16) {
-        hipLaunchKernelGGL(pool_q_bf16_kernel, gblk, dim3(128), 0, st, sa);
+        hipLaunchKernelGGL(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
         AA_LAUNCHED("pool_q_bf16_kernel");
         const int RT = 128 - 128 % kp.step;
         const dim3 gm((unsigned)cdiv(kp.N, sa.keys_per_chunk), (unsigned)cdiv(kp.nblk_max, RT),

@@ -16,6 +16,7 @@ namespace aa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 constexpr floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
 namespace {
@@ -28,35 +29,41 @@ __device__ __forceinline__ unsigned short f_to_bf16_rne(float f) {
 }  // namespace
 
 // ------------------------------------------------------------------ pool_q
-// grid (nblk_max, Hq, B), 128 threads.  bf16: writes hi/lo bf16 rows of 128; fp32: float rows of d.
-__global__ __launch_bounds__(128) void pool_q_bf16_kernel(SelectArgs a) {
+// grid (nblk_max, Hq, B).  bf16: 256 threads, thread (c, rs) sums the 16-byte chunk c of rows
+// rs, rs + 16, ...; writes hi/lo bf16 rows of 128.  fp32: 128 threads, float rows of d.
+__global__ __launch_bounds__(256) void pool_q_bf16_kernel(SelectArgs a) {
     const KParams& p = a.p;
     const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const Seq sq = seq_of(p, b);
     const int r0 = i * p.bq;
     if (r0 >= sq.len) return;
     const int r1 = min(r0 + p.bq, sq.len);
-    const int tid = threadIdx.x, dp = tid & 63, par = tid >> 6;
-    const unsigned* src = (const unsigned*)((const unsigned short*)a.q + tok_offset(p, p.qs, sq, b, h, 0));
-    const long long st = p.qs[2] / 2;  // dwords per token
-    float s0 = 0.f, s1 = 0.f;
-    for (int r = r0 + par; r < r1; r += 2) {
-        const unsigned x = src[(long long)r * st + dp];
-        s0 += __uint_as_float(x << 16);
-        s1 += __uint_as_float(x & 0xffff0000u);
+    const int tid = threadIdx.x, c = tid & 15, rs = tid >> 4;
+    const unsigned short* src = (const unsigned short*)a.q + tok_offset(p, p.qs, sq, b, h, 0) + 8 * c;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int r = r0 + rs; r < r1; r += 16) {
+        const uintx4 x = *(const uintx4*)(src + (long long)r * p.qs[2]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += __uint_as_float(x[e] << 16);
+            acc[2 * e + 1] += __uint_as_float(x[e] & 0xffff0000u);
+        }
     }
-    __shared__ float red[2][64];
-    if (par) { red[0][dp] = s0; red[1][dp] = s1; }
+    __shared__ float red[16][128];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[rs][8 * c + e] = acc[e];
     __syncthreads();
-    if (!par) {
+    if (tid < 64) {                                  // two neighbouring columns per thread
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { s0 += red[k][2 * tid]; s1 += red[k][2 * tid + 1]; }
         const float inv = 1.f / (float)(r1 - r0);
-        s0 = (s0 + red[0][dp]) * inv;
-        s1 = (s1 + red[1][dp]) * inv;
+        s0 *= inv; s1 *= inv;
         const unsigned short h0 = f_to_bf16_rne(s0), h1 = f_to_bf16_rne(s1);
         const unsigned short l0 = f_to_bf16_rne(s0 - bf16_to_f(h0)), l1 = f_to_bf16_rne(s1 - bf16_to_f(h1));
         const long long bi = blk_index(p, sq, b, h, i);
-        ((unsigned*)a.qp_hi)[bi * 64 + dp] = (unsigned)h0 | ((unsigned)h1 << 16);
-        ((unsigned*)a.qp_lo)[bi * 64 + dp] = (unsigned)l0 | ((unsigned)l1 << 16);
+        ((unsigned*)a.qp_hi)[bi * 64 + tid] = (unsigned)h0 | ((unsigned)h1 << 16);
+        ((unsigned*)a.qp_lo)[bi * 64 + tid] = (unsigned)l0 | ((unsigned)l1 << 16);
     }
 }
 
