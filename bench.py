@@ -33,17 +33,19 @@ MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
 
 
+def load_inputs(torch, synth, wl, signal, log=None):
+    t0 = time.time()
+    seq = synth.make_sequence(wl, 0, signal=signal)
+    qkv = tuple(torch.from_numpy(seq[n]).to(torch.bfloat16)[None].cuda() for n in ("q", "k", "v"))
+    if log:
+        log("inputs %s/%s ready in %.1fs" % (wl.name, signal, time.time() - t0))
+    return qkv
+
+
 def measure(api, torch, synth, wl, signal, step, steps, warmup, theta=None, dense_steps=2, log=None):
     cfg = api.Config(block=wl.block, n_init=wl.n_init, window=wl.window, step=step,
                      theta=wl.theta if theta is None else theta)
-    t0 = time.time()
-    seq = synth.make_sequence(wl, 0, signal=signal)
-    q = torch.from_numpy(seq["q"]).to(torch.bfloat16)[None].cuda()
-    k = torch.from_numpy(seq["k"]).to(torch.bfloat16)[None].cuda()
-    v = torch.from_numpy(seq["v"]).to(torch.bfloat16)[None].cuda()
-    del seq
-    if log:
-        log("inputs %s/%s ready in %.1fs" % (wl.name, signal, time.time() - t0))
+    q, k, v = load_inputs(torch, synth, wl, signal, log)
     out = torch.empty_like(q)
     p = api.make_params(cfg, q, k, v, out)
     sz = api.anchor_sizes(p)
@@ -121,6 +123,49 @@ def measure(api, torch, synth, wl, signal, step, steps, warmup, theta=None, dens
     return res, (q, k, v)
 
 
+def theta_sweep(api, torch, synth, wl, signal, step, steps, warmup, thetas, log=None):
+    """Rows of (theta, anchor on/off) -> sparsity, recall, ms per layer of the fused entry point
+    on one set of inputs: the columns of the paper's threshold ablation (Table 4)."""
+    q, k, v = load_inputs(torch, synth, wl, signal, log)
+    out = torch.empty_like(q)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    p = api.make_params(api.Config(block=wl.block, n_init=wl.n_init, window=wl.window, step=step, theta=0.0), q, k, v, out)
+    sz = api.anchor_sizes(p)
+    ws = torch.empty(sz.prefill_ws_bytes, dtype=torch.uint8, device="cuda")
+    lse = torch.empty(sz.rows, dtype=torch.float32, device="cuda")
+    dlse = torch.empty_like(lse)
+    stats = torch.zeros(4, dtype=torch.int64, device="cuda")
+    api.dense_causal_flash(p, q, k, v, out, dlse)
+    e0, e1 = ev(), ev()
+    e0.record()
+    api.dense_causal_flash(p, q, k, v, out, dlse)
+    e1.record()
+    torch.cuda.synchronize()
+    dense_ms = e0.elapsed_time(e1)
+    N = wl.seqlens[0]
+    causal_pairs = wl.Hq * N * (N + 1) // 2
+    rows = []
+    for use_anchor in (True, False):
+        for th in thetas:
+            cfg = api.Config(block=wl.block, n_init=wl.n_init, window=wl.window, step=step, theta=th,
+                             use_anchor=use_anchor)
+            p = api.make_params(cfg, q, k, v, out)
+            for _ in range(warmup):
+                api.anchor_attention_prefill(p, q, k, v, out, lse, stats, ws)
+            e0.record()
+            for _ in range(steps):
+                api.anchor_attention_prefill(p, q, k, v, out, lse, stats, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / steps
+            rows.append(dict(use_anchor=use_anchor, theta=th, sparsity=1.0 - int(stats[0]) / causal_pairs,
+                             recall=float(torch.exp(lse - dlse).double().mean()), ms_per_layer=ms,
+                             speedup_vs_dense=dense_ms / ms))
+            if log:
+                log(json.dumps(rows[-1]))
+    return dict(workload=wl.name, signal=signal, step=step, dense_flash_ms=dense_ms, rows=rows)
+
+
 def cpu_baseline(synth, wl, step, signal, budget_s=12.0):
     """Oracle (as it stands) on host cores, on whole (head 0, group) units of the same workload:
     groups are taken from the end of the sequence until about budget_s of CPU time is spent."""
@@ -151,6 +196,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-calibrated", action="store_true")
     ap.add_argument("--signal", default="literal", choices=["literal", "logit"])
+    ap.add_argument("--theta-sweep", default=None, metavar="T1,T2,...",
+                    help="instead of the benchmark line: one JSON object with sparsity / recall / ms per "
+                         "threshold, with and without the anchor (use with --signal logit)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only (the path shards by heads with no exchange step; "
@@ -162,6 +210,12 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.workloads()[args.workload]
     log = lambda s: print("[bench] " + s, file=sys.stderr, flush=True)
+
+    if args.theta_sweep:
+        thetas = [float(t) for t in args.theta_sweep.split(",")]
+        print(json.dumps(theta_sweep(api, torch, synth, wl, args.signal, args.step, args.steps, args.warmup,
+                                     thetas, log=log)), flush=True)
+        return
 
     main_res, tensors = measure(api, torch, synth, wl, args.signal, args.step, args.steps, args.warmup, log=log)
     del tensors
