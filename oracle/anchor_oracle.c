@@ -29,7 +29,10 @@
  * Parity status: every function here is pinned by tests/test_oracle_pins.py
  * (dense causal attention through a library routine at theta=+inf, a band
  * mask at theta=-inf, closed forms for constant keys, a hand-worked golden
- * example, and an independent mask-based brute force).
+ * example, and an independent mask-based brute force; the block-granularity
+ * variant by its reduction to the stripe test at b_kv = 1 and on keys that are
+ * constant inside each block, by linearity of the pooled score, and by its own
+ * brute force).
  */
 #include <math.h>
 #include <stdint.h>
@@ -159,6 +162,55 @@ int64_t ao_select_group(const ao_cfg *c, const float *k, int64_t g, int nb,
         sel[j] = (mg <= 0.0) ? 1 : 0;
         count += sel[j];
     }
+    return count;
+}
+
+/*
+ * Block-granularity identification for group g: the variant that Sec. 2.1.2 and
+ * Table 1 set against stripe granularity.  Granularity (b_q, b_kv) takes one
+ * decision per key block, granularity (b_q, 1) (ao_select_group above) one per
+ * key column.  The paper does not spell the block test out; here it is the
+ * difference test of Sec. 3.2 with the key replaced by the block's average key:
+ *   key block J = [J*b_kv, (J+1)*b_kv), a candidate iff it lies inside C_g
+ *   kbar_J      = mean of the block's keys
+ *   margin_J    = min_i ( xbar_i - sigma*<qbar_i, kbar_J> ) - theta
+ *   sel[j] = 1 and margin[j] = margin_J for every j in J iff margin_J <= 0
+ * n_init and W_g must be multiples of b_kv, so that C_g is a union of whole
+ * key blocks; returns -1 (nothing written) otherwise.  Returns |I_g|.
+ */
+int64_t ao_select_group_blocks(const ao_cfg *c, const float *k, int64_t g, int nb,
+                               const double *xbar, const double *qbar, int32_t b_kv,
+                               uint8_t *sel, double *margin)
+{
+    const int d = c->d;
+    const int64_t W = ao_window_start(c, g);
+    if (b_kv <= 0 || c->n_init % b_kv != 0 || W % b_kv != 0) return -1;
+    for (int64_t j = 0; j < c->N; ++j) {
+        sel[j] = 0;
+        if (margin) margin[j] = INFINITY;
+    }
+    int64_t count = 0;
+    double *kbar = (double *)malloc((size_t)d * sizeof(double));
+    for (int64_t J = c->n_init / b_kv; J < W / b_kv; ++J) {
+        for (int t = 0; t < d; ++t) kbar[t] = 0.0;
+        for (int64_t j = J * b_kv; j < (J + 1) * b_kv; ++j)
+            for (int t = 0; t < d; ++t) kbar[t] += (double)k[j * d + t];
+        for (int t = 0; t < d; ++t) kbar[t] /= (double)b_kv;
+        double mg = INFINITY;
+        for (int b = 0; b < nb; ++b) {
+            double s = 0.0;
+            for (int t = 0; t < d; ++t) s += qbar[b * d + t] * kbar[t];
+            double diff = xbar[b] - c->sigma * s;
+            if (diff < mg) mg = diff;
+        }
+        mg -= c->theta;
+        for (int64_t j = J * b_kv; j < (J + 1) * b_kv; ++j) {
+            if (margin) margin[j] = mg;
+            sel[j] = (mg <= 0.0) ? 1 : 0;
+            count += sel[j];
+        }
+    }
+    free(kbar);
     return count;
 }
 

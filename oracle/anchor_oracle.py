@@ -64,6 +64,8 @@ def _load():
         lib.ao_pool_block.argtypes = [P, P, P, I64, P, P]
         lib.ao_select_group.restype = I64
         lib.ao_select_group.argtypes = [P, P, I64, ctypes.c_int, P, P, P, P]
+        lib.ao_select_group_blocks.restype = I64
+        lib.ao_select_group_blocks.argtypes = [P, P, I64, ctypes.c_int, P, P, ctypes.c_int32, P, P]
         lib.ao_attend_rows.restype = I64
         lib.ao_attend_rows.argtypes = [P, P, P, P, I64, I64, P, P, P]
         _lib = lib
@@ -80,6 +82,7 @@ class OracleParams:
     step: int
     theta: float
     sigma: float | None = None  # None -> 1/sqrt(d)
+    b_kv: int = 0               # 0: stripe granularity (b_q, 1); > 0: block granularity (b_q, b_kv)
 
 
 def _ptr(a):
@@ -107,6 +110,7 @@ def run_group(q, k, v, p: OracleParams, g: int, want_acc: bool = False, attend: 
 
     Returns a dict: rows (r0,r1), M, L, (Acc), xbar[nb], qbar[nb,d], sel (uint8[N]),
     margin (float64[N]), idx (ascending int64), O, lse, pairs.
+    p.b_kv > 0 switches the selection to block granularity (one decision per key block).
     zero_anchor: selection compares against an anchor of zero (the "Without Anchor" rows of
     Table 4); M, L, Acc and xbar are still the true anchor state.
     """
@@ -135,7 +139,12 @@ def run_group(q, k, v, p: OracleParams, g: int, want_acc: bool = False, attend: 
     sel = np.empty(N, np.uint8)
     margin = np.empty(N, np.float64)
     xsel = np.zeros_like(xbar) if zero_anchor else xbar
-    cnt = lib.ao_select_group(cp, _ptr(k), g, nb, _ptr(xsel), _ptr(qbar), _ptr(sel), _ptr(margin))
+    if p.b_kv:
+        cnt = lib.ao_select_group_blocks(cp, _ptr(k), g, nb, _ptr(xsel), _ptr(qbar), p.b_kv, _ptr(sel), _ptr(margin))
+        if cnt < 0:
+            raise ValueError("block granularity needs n_init and the window start to be multiples of b_kv")
+    else:
+        cnt = lib.ao_select_group(cp, _ptr(k), g, nb, _ptr(xsel), _ptr(qbar), _ptr(sel), _ptr(margin))
     idx = np.nonzero(sel)[0].astype(np.int64)
     assert cnt == idx.size
     out = dict(rows=(r0, r1), M=M, L=L, Acc=Acc, xbar=xbar, qbar=qbar, sel=sel, margin=margin,

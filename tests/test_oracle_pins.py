@@ -270,3 +270,100 @@ def test_zero_anchor_variant_selects_on_pooled_score_alone():
         want[:ninit] = False
         want[res["W"]:] = False
         np.testing.assert_array_equal(res["sel"].astype(bool), want)
+
+
+# ------------------------------------------- block granularity (Sec. 2.1.2, Table 1)
+def test_block_granularity_with_unit_blocks_is_stripe_granularity():
+    """A key block of one column is a stripe: both tests must keep the same columns."""
+    N, d, bq, ninit, w, step, theta = 160, 8, 16, 4, 16, 2, 1.2
+    q, k, v = _rand(N, d, 21)
+    k[::6, 0] += 3.0
+    q[:, 0] += 2.0
+    stripe = ao.run_head(q, k, v, ao.OracleParams(bq, ninit, w, step, theta))
+    block = ao.run_head(q, k, v, ao.OracleParams(bq, ninit, w, step, theta, b_kv=1))
+    picked = 0
+    for a, b in zip(stripe["per_group"], block["per_group"]):
+        np.testing.assert_array_equal(a["sel"], b["sel"])
+        np.testing.assert_allclose(a["margin"], b["margin"], atol=1e-13)
+        picked += int(a["sel"].sum())
+    assert picked > 0
+    np.testing.assert_allclose(stripe["O"], block["O"], atol=1e-13)
+
+
+def test_block_margin_is_mean_of_stripe_margins_for_one_query_block():
+    """The pooled score is linear in the key, so with step = 1 (a single xbar, no min over blocks)
+    the block margin equals the mean of the stripe margins of the block's columns."""
+    N, d, bq, ninit, w, theta = 256, 16, 32, 32, 32, 0.7
+    q, k, v = _rand(N, d, 31)
+    for g in (3, 5, 7):
+        s = ao.run_group(q, k, v, ao.OracleParams(bq, ninit, w, 1, theta), g, attend=False)
+        b = ao.run_group(q, k, v, ao.OracleParams(bq, ninit, w, 1, theta, b_kv=32), g, attend=False)
+        for J in range(ninit // 32, s["W"] // 32):
+            blk = slice(32 * J, 32 * J + 32)
+            assert np.all(b["margin"][blk] == b["margin"][32 * J])
+            assert abs(b["margin"][32 * J] - s["margin"][blk].mean()) < 1e-13
+            assert np.all(b["sel"][blk] == (b["margin"][32 * J] <= 0))
+        assert not b["sel"][:ninit].any() and not b["sel"][s["W"]:].any()
+
+
+def test_block_granularity_on_blockwise_constant_keys_equals_stripe():
+    """If every key of a block equals the block mean, the two granularities see the same scores."""
+    N, d, bq, ninit, w, step, theta, bkv = 256, 8, 16, 16, 16, 2, 0.4, 16
+    q, _, v = _rand(N, d, 41)
+    rng = np.random.default_rng(42)
+    k = np.repeat(rng.standard_normal((N // bkv, d)).astype(np.float32), bkv, axis=0)
+    stripe = ao.run_head(q, k, v, ao.OracleParams(bq, ninit, w, step, theta), attend=False)
+    block = ao.run_head(q, k, v, ao.OracleParams(bq, ninit, w, step, theta, b_kv=bkv), attend=False)
+    sizes = []
+    for a, b in zip(stripe["per_group"], block["per_group"]):
+        np.testing.assert_array_equal(a["sel"], b["sel"])
+        sizes.append(a["sel"][ninit:a["W"]].mean() if a["W"] > ninit else np.nan)
+    assert 0.05 < np.nanmean(sizes) < 0.95
+
+
+@pytest.mark.parametrize("step", [1, 3])
+def test_block_granularity_matches_brute_force(step):
+    """Independent statement with full matrices: pooled queries x pooled keys, OR over the group."""
+    N, d, bq, bkv, ninit, w, theta = 288, 8, 16, 16, 16, 32, 2.2
+    q, k, v = _rand(N, d, 51 + step)
+    k[64:80] += 1.5                                  # two whole key blocks with a shifted mean
+    k[160:176] += 1.5
+    q += 0.5
+    sigma = 1.0 / math.sqrt(d)
+    res = ao.run_head(q, k, v, ao.OracleParams(bq, ninit, w, step, theta, b_kv=bkv))
+    q64, k64, v64 = (x.astype(np.float64) for x in (q, k, v))
+    S = sigma * (q64 @ k64.T)
+    rows, cols = np.arange(N)[:, None], np.arange(N)[None, :]
+    grp_of_row = (rows // bq) // step
+    Wrow = np.maximum(ninit, grp_of_row * step * bq - w)
+    anchor = (cols <= rows) & ((cols < ninit) | (cols >= Wrow))
+    M = np.where(anchor, S, -np.inf).max(1)
+    nblk = N // bq
+    xbar = M.reshape(nblk, bq).mean(1)
+    qbar = q64.reshape(nblk, bq, d).mean(1)
+    kbar = k64.reshape(N // bkv, bkv, d).mean(1)
+    diff = xbar[:, None] - sigma * (qbar @ kbar.T)   # [query block, key block]
+    mask = anchor.copy()
+    some = 0
+    for g, gr in enumerate(res["per_group"]):
+        Wg = max(ninit, g * step * bq - w)
+        blocks = diff[g * step:(g + 1) * step].min(0) <= theta
+        want = np.repeat(blocks, bkv)
+        want[:ninit] = False
+        want[Wg:] = False
+        np.testing.assert_array_equal(gr["sel"].astype(bool), want)
+        some += int(want.sum())
+        r0, r1 = gr["rows"]
+        mask[r0:r1] |= want[None, :]
+    assert 0 < some < res["pairs"]
+    Sm = np.where(mask, S, -np.inf)
+    mx = Sm.max(1, keepdims=True)
+    P = np.exp(Sm - mx)
+    np.testing.assert_allclose(res["O"], (P / P.sum(1, keepdims=True)) @ v64, atol=1e-12)
+    assert res["pairs"] == int(mask.sum())
+
+
+def test_block_granularity_rejects_unaligned_regions():
+    q, k, v = _rand(128, 8, 61)
+    with pytest.raises(ValueError):
+        ao.run_group(q, k, v, ao.OracleParams(16, 4, 16, 1, 0.0, b_kv=16), 4, attend=False)
