@@ -123,7 +123,7 @@ def measure(api, torch, synth, wl, signal, step, steps, warmup, theta=None, dens
     return res, (q, k, v)
 
 
-def theta_sweep(api, torch, synth, wl, signal, step, steps, warmup, thetas, log=None):
+def theta_sweep(api, torch, synth, wl, signal, step, steps, warmup, thetas, granularity=0, log=None):
     """Rows of (theta, anchor on/off) -> sparsity, recall, ms per layer of the fused entry point
     on one set of inputs: the columns of the paper's threshold ablation (Table 4)."""
     q, k, v = load_inputs(torch, synth, wl, signal, log)
@@ -148,7 +148,7 @@ def theta_sweep(api, torch, synth, wl, signal, step, steps, warmup, thetas, log=
     for use_anchor in (True, False):
         for th in thetas:
             cfg = api.Config(block=wl.block, n_init=wl.n_init, window=wl.window, step=step, theta=th,
-                             use_anchor=use_anchor)
+                             use_anchor=use_anchor, granularity=granularity)
             p = api.make_params(cfg, q, k, v, out)
             for _ in range(warmup):
                 api.anchor_attention_prefill(p, q, k, v, out, lse, stats, ws)
@@ -163,7 +163,8 @@ def theta_sweep(api, torch, synth, wl, signal, step, steps, warmup, thetas, log=
                              speedup_vs_dense=dense_ms / ms))
             if log:
                 log(json.dumps(rows[-1]))
-    return dict(workload=wl.name, signal=signal, step=step, dense_flash_ms=dense_ms, rows=rows)
+    return dict(workload=wl.name, signal=signal, step=step, granularity=["stripe", "block"][granularity],
+                dense_flash_ms=dense_ms, rows=rows)
 
 
 def cpu_baseline(synth, wl, step, signal, budget_s=12.0):
@@ -196,6 +197,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-calibrated", action="store_true")
     ap.add_argument("--signal", default="literal", choices=["literal", "logit"])
+    ap.add_argument("--granularity", default="stripe", choices=["stripe", "block"],
+                    help="with --theta-sweep: identification per key column (the method) or per key block")
     ap.add_argument("--theta-sweep", default=None, metavar="T1,T2,...",
                     help="instead of the benchmark line: one JSON object with sparsity / recall / ms per "
                          "threshold, with and without the anchor (use with --signal logit)")
@@ -214,7 +217,8 @@ def main():
     if args.theta_sweep:
         thetas = [float(t) for t in args.theta_sweep.split(",")]
         print(json.dumps(theta_sweep(api, torch, synth, wl, args.signal, args.step, args.steps, args.warmup,
-                                     thetas, log=log)), flush=True)
+                                     thetas, granularity=["stripe", "block"].index(args.granularity), log=log)),
+              flush=True)
         return
 
     main_res, tensors = measure(api, torch, synth, wl, args.signal, args.step, args.steps, args.warmup, log=log)

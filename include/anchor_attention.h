@@ -62,6 +62,7 @@ extern "C" {
 #endif
 
 enum { AA_FP32 = 0, AA_BF16 = 1 };
+enum { AA_STRIPE = 0, AA_BLOCK = 1 };   /* identification granularity (b_q, 1) or (b_q, b_kv) */
 
 enum {
     AA_OK = 0,
@@ -85,7 +86,8 @@ typedef struct aa_params {
     int32_t causal;           /* must be 1                                                      */
     int32_t dtype;            /* AA_FP32 or AA_BF16 (q, k, v, out)                              */
     int32_t use_anchor;       /* 1; 0 = compare against a zero anchor (Table 4, "without")      */
-    int32_t reserved;
+    int32_t granularity;      /* AA_STRIPE (0): one decision per key column, the method's own;    */
+                              /* AA_BLOCK (1): one decision per key block (see stripe_select)    */
     int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3]; /* batch, head, token; elements */
     const int32_t *cu_seqlens;/* device int32[B+1] or NULL                                      */
     int64_t total_tokens;     /* cu_seqlens[B]; ignored when cu_seqlens == NULL                 */
@@ -125,6 +127,14 @@ int anchor_compute(const aa_params *params, const void *q, const void *k, const 
  * If the lists (with padding) need more than idx_capacity entries, *overflow_flag
  * is set to 1, nothing is written past the capacity, and offsets stay exact;
  * otherwise it is set to 0.  ws: select_ws_bytes of scratch.
+ *
+ * granularity = AA_BLOCK switches to the block granularity that Sec. 2.1.2 /
+ * Table 1 set against stripes: the same difference test, taken once per key block
+ * J (block_kv consecutive keys inside C_g) on the block's average key,
+ *   xa_pooled_i - scale*<mean of block i's queries, mean of block J's keys> <= theta,
+ * and a selected block contributes all its columns to the list (same list format,
+ * so stage 3 is unchanged).  Needs n_init and window to be multiples of block_kv
+ * (AA_EINVAL otherwise).
  */
 int stripe_select(const aa_params *params, const void *q, const void *k, const float *xa_pooled,
                   int32_t *counts, int64_t *offsets, int32_t *idx, int64_t idx_capacity,

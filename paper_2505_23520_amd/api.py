@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("ANCHOR_ATTENTION_LIB", os.path.join(_HERE, "libanchor_attention.so"))
 
 AA_FP32, AA_BF16 = 0, 1
+AA_STRIPE, AA_BLOCK = 0, 1
 AA_OK, AA_EINVAL, AA_EUNSUPPORTED, AA_EWORKSPACE, AA_EHIP = 0, -1, -2, -3, -4
 
 
@@ -29,7 +30,7 @@ class aa_params(ctypes.Structure):
         ("n_init", ctypes.c_int32), ("window", ctypes.c_int32), ("step", ctypes.c_int32),
         ("theta", ctypes.c_float), ("softmax_scale", ctypes.c_float),
         ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32), ("use_anchor", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("granularity", ctypes.c_int32),
         ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
         ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
         ("cu_seqlens", ctypes.c_void_p), ("total_tokens", ctypes.c_int64),
@@ -111,6 +112,7 @@ class Config:
     softmax_scale: float = 0.0
     use_anchor: bool = True
     causal: bool = True
+    granularity: int = AA_STRIPE     # AA_BLOCK: one decision per key block (Sec. 2.1.2, Table 1)
 
 
 def _strides(t: torch.Tensor, packed: bool):
@@ -141,6 +143,7 @@ def make_params(cfg: Config, q, k, v, out=None, cu_seqlens=None, max_seqlen=None
     p.n_init, p.window, p.step = cfg.n_init, cfg.window, cfg.step
     p.theta, p.softmax_scale = cfg.theta, cfg.softmax_scale
     p.causal, p.use_anchor = int(cfg.causal), int(cfg.use_anchor)
+    p.granularity = int(cfg.granularity)
     p.dtype = {torch.float32: AA_FP32, torch.bfloat16: AA_BF16}[q.dtype]
     o = q if out is None else out
     for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", o)):

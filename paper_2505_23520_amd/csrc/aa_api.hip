@@ -40,7 +40,7 @@ struct Plan {
     aa_sizes sz;
     int nwords;
     // byte offsets inside the workspaces
-    size_t sel_qhi, sel_qlo, sel_bits;                       // stripe_select workspace
+    size_t sel_qhi, sel_qlo, sel_bits, sel_kp;               // stripe_select workspace
     size_t pf_M, pf_L, pf_Acc, pf_xa, pf_counts, pf_offsets, pf_flag, pf_idx, pf_sel;  // prefill workspace
 };
 
@@ -64,6 +64,8 @@ int make_plan(const aa_params* p, Plan* pl) {
     if (p->n_init < 0 || p->window < 0 || p->step < 1) return AA_EINVAL;
     if (std::isnan(p->theta) || std::isnan(p->softmax_scale) || p->softmax_scale < 0.f) return AA_EINVAL;
     if (p->dtype != AA_FP32 && p->dtype != AA_BF16) return AA_EINVAL;
+    if (p->granularity != AA_STRIPE && p->granularity != AA_BLOCK) return AA_EINVAL;
+    if (p->granularity == AA_BLOCK && (p->n_init % p->block_kv || p->window % p->block_kv)) return AA_EINVAL;
     if (p->cu_seqlens && (p->total_tokens <= 0 || p->N > p->total_tokens)) return AA_EINVAL;
     if (p->causal != 1) return AA_EUNSUPPORTED;
     if (p->step > 128) return AA_EUNSUPPORTED;
@@ -139,6 +141,8 @@ int make_plan(const aa_params* p, Plan* pl) {
         pl->sel_qlo = off;
     }
     pl->sel_bits = off; off += align256((size_t)s.groups * pl->nwords * 4);
+    pl->sel_kp = off;
+    if (p->granularity == AA_BLOCK) off += align256((size_t)(s.blocks / k.grp) * p->d * 4);
     s.select_ws_bytes = off;
 
     off = 0;
@@ -197,6 +201,8 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     sa.q = q; sa.k = k; sa.xa = xa;
     sa.qp_hi = ws + pl.sel_qhi; sa.qp_lo = ws + pl.sel_qlo; sa.qp_f32 = (float*)(ws + pl.sel_qhi);
     sa.bits = (unsigned*)(ws + pl.sel_bits);
+    sa.kp_f32 = (float*)(ws + pl.sel_kp);
+    sa.is_bf16 = p->dtype == AA_BF16;
     sa.nwords = pl.nwords;
     sa.keys_per_chunk = 2048;
     sa.counts = counts; sa.offsets = (long long*)offsets; sa.idx = idx;
@@ -209,7 +215,25 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
                            (long long)pl.sz.groups);
         AA_LAUNCHED("zero_i32_kernel");
     }
-    if (p->dtype == AA_BF16) {
+    if (p->granularity == AA_BLOCK) {
+        if (p->dtype == AA_BF16)
+            hipLaunchKernelGGL(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
+        else
+            hipLaunchKernelGGL(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);
+        AA_LAUNCHED("pool_q kernel");
+        hipLaunchKernelGGL(pool_k_kernel, dim3(kp.nblk_max, kp.Hkv, kp.B), dim3(128), 0, st, sa);
+        AA_LAUNCHED("pool_k_kernel");
+        static bool attr_set_blk = false;
+        if (!attr_set_blk) {
+            AA_HIP(hipFuncSetAttribute((const void*)mask_block_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       96 * 1024));
+            attr_set_blk = true;
+        }
+        const size_t lds = mask_block_lds_bytes(kp.N, kp.d, kp.bq, kp.step);
+        if (lds > 96 * 1024) return AA_EUNSUPPORTED;
+        hipLaunchKernelGGL(mask_block_kernel, ggrp, dim3(256), lds, st, sa);
+        AA_LAUNCHED("mask_block_kernel");
+    } else if (p->dtype == AA_BF16) {
         hipLaunchKernelGGL(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
         AA_LAUNCHED("pool_q_bf16_kernel");
         const int RT = 128 - 128 % kp.step;

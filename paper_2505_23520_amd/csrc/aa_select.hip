@@ -248,6 +248,102 @@ __global__ __launch_bounds__(256) void mask_fp32_kernel(SelectArgs a) {
     if (lane == 32 && w0 + 1 < a.nwords) a.bits[t * a.nwords + w0 + 1] = (unsigned)(bal >> 32);
 }
 
+// ------------------------------------------------------------------ block granularity
+// One decision per key block (Sec. 2.1.2 / Table 1's block granularity) instead of one per column:
+// the difference test of Sec. 3.2 on the block's average key.  Tiny next to the stripe mask
+// (pooled rows x pooled keys), so plain fp32 FMAs.
+
+// kbar_J = mean of key block J.  grid (nblk_max, Hkv, B), 128 threads: one column per thread.
+__global__ __launch_bounds__(128) void pool_k_kernel(SelectArgs a) {
+    const KParams& p = a.p;
+    const int J = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const Seq sq = seq_of(p, b);
+    const int r0 = J * p.bq;
+    if (r0 >= sq.len) return;
+    const int r1 = min(r0 + p.bq, sq.len);
+    const long long kb = (p.packed ? (long long)hk * p.blk_cap + sq.blk0 : ((long long)b * p.Hkv + hk) * p.blk_cap) + J;
+    const long long base = tok_offset(p, p.ks, sq, b, hk, 0);
+    for (int c = threadIdx.x; c < p.d; c += blockDim.x) {
+        float s = 0.f;
+        if (a.is_bf16) {
+            const unsigned short* src = (const unsigned short*)a.k + base + c;
+            for (int r = r0; r < r1; ++r) s += bf16_to_f(src[(long long)r * p.ks[2]]);
+        } else {
+            const float* src = (const float*)a.k + base + c;
+            for (int r = r0; r < r1; ++r) s += src[(long long)r * p.ks[2]];
+        }
+        a.kp_f32[kb * p.d + c] = s / (float)(r1 - r0);
+    }
+}
+
+// dynamic LDS of mask_block_kernel: step pooled query rows, step anchors, one flag per key block
+size_t mask_block_lds_bytes(int N, int d, int bq, int step) {
+    return (size_t)step * d * 4 + (size_t)step * 4 + (size_t)((N / bq + 15) / 16) * 16;
+}
+
+// grid (ngrp_max, Hq, B), 256 threads = 16 key blocks x 16 pooled-row slots per pass.
+// Needs n_init and the window start to be multiples of bq, so every half word (16 keys) of the
+// bit map lies inside one key block and inside or outside C_g as a whole.
+__global__ __launch_bounds__(256) void mask_block_kernel(SelectArgs a) {
+    const KParams& p = a.p;
+    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z, hk = h / p.grp;
+    const Seq sq = seq_of(p, b);
+    const int nblk = (sq.len + p.bq - 1) / p.bq;
+    const int i0 = g * p.step;
+    if (i0 >= nblk) return;
+    const int nb = min(p.step, nblk - i0);
+    const int Wg = window_start(p, g);
+    if (Wg <= p.n_init) return;
+    const int d = p.d, tid = threadIdx.x;
+    extern __shared__ __attribute__((aligned(16))) float bsm[];
+    float* qs = bsm;                                   // [step][d]
+    float* xs = bsm + p.step * d;                      // [step]
+    unsigned char* flag = (unsigned char*)(xs + p.step);   // [key blocks of C_g]
+    for (int e = tid; e < nb * d; e += 256) {
+        const long long bi = blk_index(p, sq, b, h, i0 + e / d);
+        const int c = e % d;
+        qs[e] = a.is_bf16 ? bf16_to_f(((const unsigned short*)a.qp_hi)[bi * 128 + c]) +
+                                bf16_to_f(((const unsigned short*)a.qp_lo)[bi * 128 + c])
+                          : a.qp_f32[bi * d + c];
+    }
+    for (int s = tid; s < nb; s += 256) xs[s] = p.use_anchor ? a.xa[blk_index(p, sq, b, h, i0 + s)] : 0.f;
+    __syncthreads();
+    const int J_lo = p.n_init / p.bq, J_hi = Wg / p.bq;
+    const long long kb0 = p.packed ? (long long)hk * p.blk_cap + sq.blk0 : ((long long)b * p.Hkv + hk) * p.blk_cap;
+    const int Jl = tid >> 4, sl = tid & 15;
+    for (int J0 = J_lo; J0 < J_hi; J0 += 16) {
+        const int J = J0 + Jl;
+        int pred = 0;
+        if (J < J_hi) {
+            const float4* kr = (const float4*)(a.kp_f32 + (kb0 + J) * d);
+            for (int s = sl; s < nb; s += 16) {
+                const float4* qr = (const float4*)(qs + s * d);
+                float dot = 0.f;
+                for (int c = 0; c < d / 4; ++c) {
+                    const float4 x = qr[c], y = kr[c];
+                    dot = fmaf(x.x, y.x, dot); dot = fmaf(x.y, y.y, dot);
+                    dot = fmaf(x.z, y.z, dot); dot = fmaf(x.w, y.w, dot);
+                }
+                pred |= ((xs[s] - p.sigma * dot) <= p.theta) ? 1 : 0;
+            }
+        }
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) pred |= __shfl_xor(pred, off, 64);
+        if (sl == 0 && J < J_hi) flag[J - J_lo] = (unsigned char)pred;
+    }
+    __syncthreads();
+    unsigned* bits = a.bits + grp_index(p, sq, b, h, g) * a.nwords;
+    for (int w = p.n_init / 32 + tid; w < (Wg + 31) / 32; w += 256) {
+        unsigned wd = 0;
+#pragma unroll
+        for (int hw = 0; hw < 2; ++hw) {
+            const int j = 32 * w + 16 * hw;
+            if (j >= p.n_init && j < Wg && flag[j / p.bq - J_lo]) wd |= 0xffffu << (16 * hw);
+        }
+        bits[w] = wd;
+    }
+}
+
 // ------------------------------------------------------------------ count / scan / fill
 __global__ void zero_i32_kernel(int* x, long long nelem) {
     long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;

@@ -112,7 +112,8 @@ class GpuRun:
 
 def oracle_params(cfg, d):
     return ao.OracleParams(b_q=cfg.block, n_init=cfg.n_init, w=cfg.window, step=cfg.step,
-                           theta=float(cfg.theta), sigma=(cfg.softmax_scale or None))
+                           theta=float(cfg.theta), sigma=(cfg.softmax_scale or None),
+                           b_kv=cfg.block if getattr(cfg, "granularity", 0) == 1 else 0)
 
 
 def tolerances(dtype):

@@ -46,11 +46,15 @@ def test_sizes_arithmetic(api):
     assert s.prefill_ws_bytes > s.select_ws_bytes > 0
     s1 = api.anchor_sizes(_params(api, step=1))
     assert s1.groups == 32 * 64
+    # block granularity adds the pooled keys (8 KV heads x 64 blocks x 128 floats) to the workspace
+    sb = api.anchor_sizes(_params(api, granularity=api.AA_BLOCK))
+    assert sb.select_ws_bytes == s.select_ws_bytes + 8 * 64 * 128 * 4
 
 
 @pytest.mark.parametrize("kw,code", [
     (dict(Hkv=5), -1), (dict(N=0), -1), (dict(step=0), -1), (dict(block_kv=64), -1), (dict(n_init=-1), -1),
-    (dict(theta=float("nan")), -1), (dict(dtype=7), -1),
+    (dict(theta=float("nan")), -1), (dict(dtype=7), -1), (dict(granularity=2), -1),
+    (dict(granularity=1, n_init=64), -1), (dict(granularity=1, window=100), -1),
     (dict(causal=0), -2), (dict(d=64), -2), (dict(step=129), -2), (dict(block_q=64, block_kv=64), -2),
 ])
 def test_rejects_bad_params(api, kw, code):
