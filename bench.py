@@ -129,7 +129,8 @@ def theta_sweep(api, torch, synth, wl, signal, step, steps, warmup, thetas, gran
     q, k, v = load_inputs(torch, synth, wl, signal, log)
     out = torch.empty_like(q)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    p = api.make_params(api.Config(block=wl.block, n_init=wl.n_init, window=wl.window, step=step, theta=0.0), q, k, v, out)
+    p = api.make_params(api.Config(block=wl.block, n_init=wl.n_init, window=wl.window, step=step, theta=0.0,
+                                   granularity=granularity), q, k, v, out)
     sz = api.anchor_sizes(p)
     ws = torch.empty(sz.prefill_ws_bytes, dtype=torch.uint8, device="cuda")
     lse = torch.empty(sz.rows, dtype=torch.float32, device="cuda")

@@ -226,11 +226,11 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
         static bool attr_set_blk = false;
         if (!attr_set_blk) {
             AA_HIP(hipFuncSetAttribute((const void*)mask_block_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       96 * 1024));
+                                       128 * 1024));
             attr_set_blk = true;
         }
         const size_t lds = mask_block_lds_bytes(kp.N, kp.d, kp.bq, kp.step);
-        if (lds > 96 * 1024) return AA_EUNSUPPORTED;
+        if (lds > 128 * 1024) return AA_EUNSUPPORTED;
         hipLaunchKernelGGL(mask_block_kernel, ggrp, dim3(256), lds, st, sa);
         AA_LAUNCHED("mask_block_kernel");
     } else if (p->dtype == AA_BF16) {

@@ -276,17 +276,22 @@ __global__ __launch_bounds__(128) void pool_k_kernel(SelectArgs a) {
     }
 }
 
-// dynamic LDS of mask_block_kernel: step pooled query rows, step anchors, one flag per key block
+// dynamic LDS of mask_block_kernel: step pooled query rows, step anchors, a tile of 64 pooled keys
+// (rows padded by 4 floats), one flag per key block
+constexpr int kBlkTile = 64;
 size_t mask_block_lds_bytes(int N, int d, int bq, int step) {
-    return (size_t)step * d * 4 + (size_t)step * 4 + (size_t)((N / bq + 15) / 16) * 16;
+    return (size_t)step * d * 4 + (size_t)step * 4 + (size_t)kBlkTile * (d + 4) * 4 + (size_t)((N / bq + 15) / 16) * 16;
 }
 
-// grid (ngrp_max, Hq, B), 256 threads = 16 key blocks x 16 pooled-row slots per pass.
+// grid (ngrp_max, Hq, B), 256 threads.  Per pass a tile of 64 pooled keys sits in LDS; lane l of
+// every wave owns key block l of the tile, wave w the pooled rows w, w + 4, ... of the group (so
+// the query operand is a broadcast read), four rows at a time.
 // Needs n_init and the window start to be multiples of bq, so every half word (16 keys) of the
 // bit map lies inside one key block and inside or outside C_g as a whole.
 __global__ __launch_bounds__(256) void mask_block_kernel(SelectArgs a) {
     const KParams& p = a.p;
-    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z, hk = h / p.grp;
+    const int g = p.ngrp_max - 1 - (int)blockIdx.x;    // long candidate ranges first
+    const int h = blockIdx.y, b = blockIdx.z, hk = h / p.grp;
     const Seq sq = seq_of(p, b);
     const int nblk = (sq.len + p.bq - 1) / p.bq;
     const int i0 = g * p.step;
@@ -294,11 +299,13 @@ __global__ __launch_bounds__(256) void mask_block_kernel(SelectArgs a) {
     const int nb = min(p.step, nblk - i0);
     const int Wg = window_start(p, g);
     if (Wg <= p.n_init) return;
-    const int d = p.d, tid = threadIdx.x;
+    const int d = p.d, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int kst = d + 4;                             // floats per row of the key tile
     extern __shared__ __attribute__((aligned(16))) float bsm[];
     float* qs = bsm;                                   // [step][d]
-    float* xs = bsm + p.step * d;                      // [step]
-    unsigned char* flag = (unsigned char*)(xs + p.step);   // [key blocks of C_g]
+    float* xs = qs + p.step * d;                       // [step]
+    float* kt = xs + p.step;                           // [64][d + 4]
+    unsigned char* flag = (unsigned char*)(kt + kBlkTile * kst);   // [key blocks of C_g]
     for (int e = tid; e < nb * d; e += 256) {
         const long long bi = blk_index(p, sq, b, h, i0 + e / d);
         const int c = e % d;
@@ -307,29 +314,43 @@ __global__ __launch_bounds__(256) void mask_block_kernel(SelectArgs a) {
                           : a.qp_f32[bi * d + c];
     }
     for (int s = tid; s < nb; s += 256) xs[s] = p.use_anchor ? a.xa[blk_index(p, sq, b, h, i0 + s)] : 0.f;
-    __syncthreads();
     const int J_lo = p.n_init / p.bq, J_hi = Wg / p.bq;
     const long long kb0 = p.packed ? (long long)hk * p.blk_cap + sq.blk0 : ((long long)b * p.Hkv + hk) * p.blk_cap;
-    const int Jl = tid >> 4, sl = tid & 15;
-    for (int J0 = J_lo; J0 < J_hi; J0 += 16) {
-        const int J = J0 + Jl;
+    const int d4 = d / 4;
+    for (int J0 = J_lo; J0 < J_hi; J0 += kBlkTile) {
+        const int nJ = min(kBlkTile, J_hi - J0);
+        __syncthreads();                               // previous tile consumed (first pass: qs, xs written)
+        for (int e = tid; e < nJ * d4; e += 256) {
+            const int r = e / d4, c = e % d4;
+            *(float4*)(kt + r * kst + 4 * c) = *(const float4*)(a.kp_f32 + (kb0 + J0 + r) * d + 4 * c);
+        }
+        __syncthreads();
         int pred = 0;
-        if (J < J_hi) {
-            const float4* kr = (const float4*)(a.kp_f32 + (kb0 + J) * d);
-            for (int s = sl; s < nb; s += 16) {
-                const float4* qr = (const float4*)(qs + s * d);
-                float dot = 0.f;
-                for (int c = 0; c < d / 4; ++c) {
-                    const float4 x = qr[c], y = kr[c];
-                    dot = fmaf(x.x, y.x, dot); dot = fmaf(x.y, y.y, dot);
-                    dot = fmaf(x.z, y.z, dot); dot = fmaf(x.w, y.w, dot);
+        if (lane < nJ) {
+            const float4* kr = (const float4*)(kt + lane * kst);
+            for (int s0 = wave; s0 < nb; s0 += 16) {   // rows s0, s0 + 4, s0 + 8, s0 + 12
+                float dot[4] = {0.f, 0.f, 0.f, 0.f};
+                for (int c = 0; c < d4; ++c) {
+                    const float4 y = kr[c];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int s = min(s0 + 4 * e, nb - 1);
+                        const float4 x = *(const float4*)(qs + s * d + 4 * c);
+                        dot[e] = fmaf(x.x, y.x, dot[e]); dot[e] = fmaf(x.y, y.y, dot[e]);
+                        dot[e] = fmaf(x.z, y.z, dot[e]); dot[e] = fmaf(x.w, y.w, dot[e]);
+                    }
                 }
-                pred |= ((xs[s] - p.sigma * dot) <= p.theta) ? 1 : 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int s = min(s0 + 4 * e, nb - 1);    // a clamped row repeats a real one: same OR
+                    pred |= ((xs[s] - p.sigma * dot[e]) <= p.theta) ? 1 : 0;
+                }
             }
         }
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) pred |= __shfl_xor(pred, off, 64);
-        if (sl == 0 && J < J_hi) flag[J - J_lo] = (unsigned char)pred;
+        // OR over the four waves: each wave ORs its bit into the block's flag byte
+        if (wave == 0 && lane < nJ) flag[J0 - J_lo + lane] = (unsigned char)pred;
+        __syncthreads();
+        if (wave != 0 && lane < nJ && pred) flag[J0 - J_lo + lane] = 1;   // same value from every writer
     }
     __syncthreads();
     unsigned* bits = a.bits + grp_index(p, sq, b, h, g) * a.nwords;
