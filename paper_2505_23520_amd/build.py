@@ -9,10 +9,10 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libanchor_attention.so")
-SOURCES = ["aa_api.hip", "aa_engine_bf16.hip", "aa_engine_fp32.hip", "aa_select.hip"]
-# The bf16 engine never produces a NaN that is used (masked scores are -inf, the guards around
-# exp(-inf - -inf) select the other arm), so its row-max chains may drop NaN canonicalisation.
-EXTRA = {"aa_engine_bf16.hip": ["-fno-honor-nans"]}
+SOURCES = ["aa_api.hip", "aa_engine_bf16.hip", "aa_engine_bf16_pp.hip", "aa_engine_fp32.hip", "aa_select.hip"]
+# The bf16 engines never produce a NaN that is used (masked scores are -inf, the guards around
+# exp(-inf - -inf) select the other arm), so their row-max chains may drop NaN canonicalisation.
+EXTRA = {"aa_engine_bf16.hip": ["-fno-honor-nans"], "aa_engine_bf16_pp.hip": ["-fno-honor-nans"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-unused-command-line-argument",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -32,7 +32,7 @@ def build(verbose: bool = False) -> str:
             sys.stderr.write(r.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=5) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
                        capture_output=True, text=True)

@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "../../include/anchor_attention.h"
@@ -165,8 +166,17 @@ int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
     const KParams& k = pl.kp;
     const unsigned grid = (unsigned)((long long)k.nblk_max * k.Hq * k.B);
     if (dtype == AA_BF16) {
-        hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(256), 0, st, ea);
-        AA_LAUNCHED("engine_bf16_kernel");
+        // experimental 256-row ping-pong engine (needs both blocks of a pair to share window and
+        // list); not faster than the 128-row engine yet, so it is opt-in
+        static const bool use_pp = getenv("ANCHOR_ATTENTION_ENGINE_PP") != nullptr;
+        if (((ea.flags & kEngDense) || k.step % 2 == 0) && use_pp) {
+            const unsigned gridp = (unsigned)((long long)((k.nblk_max + 1) / 2) * k.Hq * k.B);
+            hipLaunchKernelGGL(engine_bf16_pp_kernel, dim3(gridp), dim3(512), 0, st, ea);
+            AA_LAUNCHED("engine_bf16_pp_kernel");
+        } else {
+            hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(256), 0, st, ea);
+            AA_LAUNCHED("engine_bf16_kernel");
+        }
     } else {
         const size_t lds = engine_fp32_lds_bytes(k.d, k.bq);
         static bool attr_set32 = false;

@@ -27,6 +27,8 @@ struct EngineArgs {
 };
 
 __global__ void engine_bf16_kernel(EngineArgs a);
+// 256 query rows (two consecutive blocks) per work-group; needs dense mode or an even step
+__global__ void engine_bf16_pp_kernel(EngineArgs a);
 
 __global__ void engine_fp32_kernel(EngineArgs a);
 size_t engine_fp32_lds_bytes(int d, int bq);
