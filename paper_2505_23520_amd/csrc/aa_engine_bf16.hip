@@ -62,14 +62,20 @@ typedef __attribute__((address_space(3))) void lds_void;
 // s_waitcnt vmcnt(0) only (gfx9 encoding: expcnt and lgkmcnt fields left at their maxima)
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
-__device__ __forceinline__ float xhalf(float x) {  // value held by the lane 32 away
-    return __shfl_xor(x, 32, 64);
+// x of this lane and x of the lane 32 away, in an order that depends on the half (fine for
+// max and sum); v_permlane32_swap is a plain VALU operation, no trip through the LDS crossbar
+__device__ __forceinline__ void both_halves(float x, float& u, float& v) {
+    const unsigned b = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+    u = __uint_as_float(r[0]);
+    v = __uint_as_float(r[1]);
 }
 
 }  // namespace
 
 __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     constexpr int NW = 4;                            // waves per work-group
+    static_assert(NW == 4, "the loader deals four groups of a tile to every wave");
     // one LDS object per stage, so that the compiler can tell that the asynchronous loads into
     // one stage do not alias the operand reads from the other
     __shared__ __attribute__((aligned(16))) char Ks0[KBYTES], Ks1[KBYTES], Vs0[VBYTES], Vs1[VBYTES];
@@ -134,31 +140,36 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     auto tile_start = [&](int t) -> int {            // first key of contiguous tile t (t < nA)
         return TK * (t < T1 ? t : t2s + (t - T1));
     };
-    auto tile_keys = [&](int t, int* key) {
+    // Keys of a list tile come from the index list: they are fetched one step ahead into kidx.
+    // Nothing else ever writes kidx's registers: a vector-ALU write to registers that may still
+    // be the target of an outstanding load makes the compiler wait for every outstanding load,
+    // the asynchronous tile loads included.  Keys of a contiguous tile are plain arithmetic.
+    intx4 kidx = {0, 0, 0, 0};
+    auto idx_prefetch = [&](int t) {
+        if (t >= nA && t < nT) kidx = *(const intx4*)(a.idx + lbase + (long long)(t - nA) * TK + kq0);
+    };
+    // asynchronous: completion is awaited by wait_vmem()
+    auto tile_load = [&](int t, char* Kb, char* Vb) {
+        char* kd = Kb + GPW * wave * KGRP;
+        char* vd = Vb + GPW * wave * VGRP;
         if (t < nA) {
             const int t0 = tile_start(t) + kq0;
 #pragma unroll
-            for (int e = 0; e < GPW; ++e) key[e] = min(t0 + e, sq.len - 1);
-        } else {
-            const int* src = a.idx + lbase + (long long)(t - nA) * TK + kq0;
-            if constexpr (GPW == 4) {
-                const intx4 x = *(const intx4*)src;
-                key[0] = x.x; key[1] = x.y; key[2] = x.z; key[3] = x.w;
-            } else {
-                const intx2 x = *(const intx2*)src;
-                key[0] = x.x; key[1] = x.y;
+            for (int j = 0; j < GPW; ++j) {
+                const unsigned key = (unsigned)min(t0 + j, sq.len - 1);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(kd + j * KGRP), 16,
+                                                         (int)(key * kstb + 16u * lch), 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(vrs, (lds_void*)(vd + j * VGRP), 16,
+                                                         (int)(key * vstb + 16u * lch), 0, 0, 0);
             }
-        }
-    };
-    // asynchronous: completion is awaited by wait_vmem()
-    auto tile_load = [&](const int* key, char* Kb, char* Vb) {
+        } else {
 #pragma unroll
-        for (int j = 0; j < GPW; ++j) {
-            const int gi = GPW * wave + j;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(Kb + gi * KGRP), 16,
-                                                     (int)((unsigned)key[j] * kstb + 16u * lch), 0, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(vrs, (lds_void*)(Vb + gi * VGRP), 16,
-                                                     (int)((unsigned)key[j] * vstb + 16u * lch), 0, 0, 0);
+            for (int j = 0; j < GPW; ++j) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(kd + j * KGRP), 16,
+                                                         (int)((unsigned)kidx[j] * kstb + 16u * lch), 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(vrs, (lds_void*)(vd + j * VGRP), 16,
+                                                         (int)((unsigned)kidx[j] * vstb + 16u * lch), 0, 0, 0);
+            }
         }
     };
 
@@ -204,11 +215,10 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     }
 
     // ---- pipeline prologue
-    int keys[GPW];
     if (nT > 0) {
-        tile_keys(0, keys);
-        tile_load(keys, Ks0, Vs0);
-        if (nT > 1) tile_keys(1, keys);
+        idx_prefetch(0);
+        tile_load(0, Ks0, Vs0);
+        idx_prefetch(1);
     }
     wait_vmem();
     __syncthreads();
@@ -221,8 +231,8 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
 
     auto tile_step = [&](int t, const char* Kcur, const char* Vcur, char* Knext, char* Vnext) {
         if (t + 1 < nT) {
-            tile_load(keys, Knext, Vnext);
-            if (t + 2 < nT) tile_keys(t + 2, keys);
+            tile_load(t + 1, Knext, Vnext);
+            idx_prefetch(t + 2);
         }
         const char* Kb = Kcur + koff;
         const char* Vb = Vcur + voff;
@@ -285,8 +295,12 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         // online softmax of this lane's query row (the other half of the row is 32 lanes away)
         float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s[0][v], s[1][v]));
-        mx = fmaxf(mx, xhalf(mx));
+        for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, s[0][v]), s[1][v]);     // v_max3_f32
+        {
+            float u, w;
+            both_halves(mx, u, w);
+            mx = fmaxf(u, w);
+        }
         mtrue = fmaxf(mtrue, mx);
         if (__any(mx > mref + rescale_gap)) {                 // rare after the first tiles
             const float mnew = fmaxf(mref, mx);
@@ -340,7 +354,12 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     }
 
     // ---- epilogue
-    const float lt = l + xhalf(l);                   // row sum relative to mref
+    float lt;                                        // row sum relative to mref
+    {
+        float u, w;
+        both_halves(l, u, w);
+        lt = u + w;
+    }
     if (a.flags & kEngStoreState) {
         // exported state is relative to the true maximum (Algorithm 1's m, l, acc)
         const float down = (mref == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mtrue) * c2);
