@@ -106,6 +106,16 @@ typedef struct aa_sizes {
     size_t  prefill_ws_bytes; /* workspace of anchor_attention_prefill                          */
 } aa_sizes;
 
+/*
+ * Tuning / testing aid, not part of the method: which of the two bf16 tile engines the
+ * following calls of this process use.  0 (default): chosen per launch (by sequence length for
+ * dense attention, on the device by the mean list length for stage 3, always the 128-row engine
+ * for stage 1); 1: the engine with 128 query rows per work-group; 2: the engine with 256 query
+ * rows per work-group wherever it applies (dense attention, even step).  Results agree to
+ * rounding.  Not thread-safe against concurrent calls.  AA_EINVAL for other values.
+ */
+int anchor_set_engine(int mode);
+
 /* Validates params (AA_EINVAL / AA_EUNSUPPORTED) and fills *out.  Host only. */
 int anchor_sizes(const aa_params *params, aa_sizes *out);
 

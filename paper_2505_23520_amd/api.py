@@ -68,12 +68,14 @@ _lib.dense_causal_flash.restype = ctypes.c_int
 _lib.dense_causal_flash.argtypes = [_PP, _P, _P, _P, _P, _P, _P]
 _lib.anchor_probe_mfma.restype = ctypes.c_int
 _lib.anchor_probe_mfma.argtypes = [ctypes.c_int, _P, _P]
+_lib.anchor_set_engine.restype = ctypes.c_int
+_lib.anchor_set_engine.argtypes = [ctypes.c_int]
 _lib.anchor_strerror.restype = ctypes.c_char_p
 _lib.anchor_strerror.argtypes = [ctypes.c_int]
 _lib.anchor_last_hip_error.restype = ctypes.c_char_p
 _lib.anchor_last_hip_error.argtypes = []
 
-EXPORTS = ("anchor_sizes", "anchor_compute", "stripe_select", "sparse_attn", "anchor_attention_prefill",
+EXPORTS = ("anchor_set_engine", "anchor_sizes", "anchor_compute", "stripe_select", "sparse_attn", "anchor_attention_prefill",
            "dense_causal_flash", "anchor_probe_mfma", "anchor_strerror", "anchor_last_hip_error")
 
 
@@ -183,6 +185,11 @@ def anchor_attention_prefill(p, q, k, v, out, lse, stats, ws, stream=None):
 def dense_causal_flash(p, q, k, v, out, lse=None, stream=None):
     _check(_lib.dense_causal_flash(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
                                    _stream(stream)))
+
+
+def anchor_set_engine(mode: int):
+    """0: engine chosen per launch; 1 / 2: force the 128-row / 256-row bf16 engine (testing aid)."""
+    _check(_lib.anchor_set_engine(int(mode)))
 
 
 def anchor_probe_mfma(iters, scratch, stream=None):

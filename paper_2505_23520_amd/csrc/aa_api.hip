@@ -5,7 +5,6 @@
 
 #include <cmath>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 
 #include "../../include/anchor_attention.h"
@@ -17,6 +16,7 @@ namespace aa {
 namespace {
 
 thread_local char g_hip_err[256] = "";
+int g_engine_mode = 0;   // anchor_set_engine
 
 int hip_fail(hipError_t e, const char* what) {
     snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
@@ -166,11 +166,30 @@ int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
     const KParams& k = pl.kp;
     const unsigned grid = (unsigned)((long long)k.nblk_max * k.Hq * k.B);
     if (dtype == AA_BF16) {
-        // experimental 256-row ping-pong engine (needs both blocks of a pair to share window and
-        // list); not faster than the 128-row engine yet, so it is opt-in
-        static const bool use_pp = getenv("ANCHOR_ATTENTION_ENGINE_PP") != nullptr;
-        if (((ea.flags & kEngDense) || k.step % 2 == 0) && use_pp) {
-            const unsigned gridp = (unsigned)((long long)((k.nblk_max + 1) / 2) * k.Hq * k.B);
+        // Two bf16 engines: 128 query rows per work-group (two work-groups per CU) and 256 rows
+        // per work-group with the MFMA / softmax phases of the two waves of a SIMD alternating.
+        // The second is faster on long tile loops and slower on short ones (its prologue and
+        // epilogue overlap with nothing); it needs both blocks of a pair to share window and list.
+        const bool pair_ok = (ea.flags & kEngDense) || k.step % 2 == 0;
+        int choice = g_engine_mode;                 // 0 auto, 1: 128 rows, 2: 256 rows
+        if (!pair_ok) choice = 1;
+        ea.sel = 0;
+        if (choice == 0) {
+            if (ea.flags & kEngList) choice = 3;    // decided on the device from the list lengths
+            else if (ea.flags & kEngDense) choice = k.N >= 8192 ? 2 : 1;
+            else choice = 1;                        // anchor region alone: at most step + 3 blocks of keys
+        }
+        const unsigned gridp = (unsigned)((long long)((k.nblk_max + 1) / 2) * k.Hq * k.B);
+        if (choice == 3) {
+            ea.sel_groups = pl.sz.groups;
+            ea.sel_entries = 48ll * 64 * pl.sz.groups;   // mean list of 48 tiles
+            ea.sel = 1;
+            hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(256), 0, st, ea);
+            AA_LAUNCHED("engine_bf16_kernel");
+            ea.sel = 2;
+            hipLaunchKernelGGL(engine_bf16_pp_kernel, dim3(gridp), dim3(512), 0, st, ea);
+            AA_LAUNCHED("engine_bf16_pp_kernel");
+        } else if (choice == 2) {
             hipLaunchKernelGGL(engine_bf16_pp_kernel, dim3(gridp), dim3(512), 0, st, ea);
             AA_LAUNCHED("engine_bf16_pp_kernel");
         } else {
@@ -330,6 +349,12 @@ __global__ void zero_u64_kernel(unsigned long long* x, int nelem) {
 using namespace aa;
 
 extern "C" {
+
+int anchor_set_engine(int mode) {
+    if (mode < 0 || mode > 2) return AA_EINVAL;
+    g_engine_mode = mode;
+    return AA_OK;
+}
 
 int anchor_sizes(const aa_params* params, aa_sizes* out) {
     Plan pl;

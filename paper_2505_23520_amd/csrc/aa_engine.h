@@ -24,7 +24,19 @@ struct EngineArgs {
     float *Mout, *Lout, *Accout, *xa;
     void* out;
     float* lse;
+    // Two engines can be launched for the same list-driven call; each decides on the device from
+    // the total (padded) list length offsets[sel_groups] whether it is the one to run:
+    // sel = 0 runs always, sel = 1 runs iff the total is below sel_entries, sel = 2 iff not.
+    int sel;
+    long long sel_groups, sel_entries;
 };
+
+// true iff this launch is the one that was chosen (uniform over the grid)
+__device__ __forceinline__ bool engine_selected(const EngineArgs& a) {
+    if (a.sel == 0) return true;
+    const bool big = a.offsets[a.sel_groups] >= a.sel_entries;
+    return (a.sel == 2) == big;
+}
 
 __global__ void engine_bf16_kernel(EngineArgs a);
 // 256 query rows (two consecutive blocks) per work-group; needs dense mode or an even step

@@ -86,6 +86,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
     const int n = lane & 31, hf = lane >> 5;
 
+    if (!engine_selected(a)) return;
     const Work wk = decode_work(p, p.nblk_max, blockIdx.x);
     const Seq sq = seq_of(p, wk.b);
     const int row0 = wk.i * BQ;

@@ -5,14 +5,14 @@
 //   work-group = two consecutive query blocks of one head = 8 waves x 32 query rows, one
 //   work-group per CU.  Waves w and w + 4 share a SIMD; waves 0-3 form group A, waves 4-7
 //   group B.  Time is cut into slots by work-group barriers.  In every slot one group runs its
-//   MFMA phase (O^T += V^T P^T of tile t, then S^T = K Q^T of tile t + 1: 32 MFMAs) while the
-//   other runs its softmax phase (row max, exp2, row sum, bf16 conversion of tile t on the
-//   vector ALU, and the 32 transposing LDS reads that fetch the tile's V^T operands into
-//   registers); then they swap.  Group B runs one slot behind group A.
+//   MFMA phase (S^T = K Q^T of tile t + 1, then O^T += V^T P^T of tile t: 32 MFMAs interleaved
+//   with their LDS operand reads) while the other runs its softmax phase (row max, exp2, row
+//   sum, bf16 conversion of tile t on the vector ALU, and the issue of this wave's share of the
+//   tile loads); then they swap.  Group B runs one slot behind group A.
 //   K/V tiles are triple-buffered in LDS and shared by the 256 rows.  Group A's waves issue the
-//   direct-to-LDS loads of the K tiles, group B's those of the V tiles, three tiles ahead, at the
-//   start of an MFMA phase, and wait for them at the start of their next MFMA phase (two slots
-//   later).
+//   direct-to-LDS loads of the K tiles (three tiles ahead), group B's those of the V tiles (two
+//   tiles ahead), from inside their MFMA phase, and wait for them at the start of their next
+//   MFMA phase (two slots later).  Masks are applied to the scores in the softmax phase.
 // The two query blocks must share their window start and their selected-column list: the host
 // launches this kernel for dense attention and for even `step`, the 128-row kernel otherwise.
 #include "aa_common.h"
@@ -82,6 +82,7 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
     const int simd = wave & 3;
     const int chunk = 2 * simd + grpB;               // the wave's 32 rows inside the pair
 
+    if (!engine_selected(a)) return;
     const int npair = (p.nblk_max + 1) >> 1;
     const Work wk = decode_work(p, npair, blockIdx.x);   // wk.i = pair index
     const Seq sq = seq_of(p, wk.b);
@@ -132,13 +133,18 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
     auto tile_start = [&](int t) -> int {            // first key of contiguous tile t (t < nA)
         return TK * (t < T1 ? t : t2s + (t - T1));
     };
-    // Keys of a list tile come from the index list: they are fetched one step ahead into kidx.
-    // Nothing else ever writes kidx's registers: a vector-ALU write to registers that may still
-    // be the target of an outstanding load makes the compiler wait for every outstanding load,
-    // the asynchronous tile loads included.  Keys of a contiguous tile are plain arithmetic.
-    intx4 kidx = {0, 0, 0, 0};
-    auto idx_prefetch = [&](int t) {
-        if (t >= nA && t < nT) kidx = *(const intx4*)(a.idx + lbase + (long long)(t - nA) * TK + kq0);
+    // Keys of a list tile come from the index list.  The MFMA phase of round position i (tile
+    // number mod 3) takes the keys of the tile it loads from kidx[i]; they are fetched there two
+    // phases earlier.  Nothing else ever writes these registers: a vector-ALU write to registers
+    // that may still be the target of an outstanding load makes the compiler wait for every
+    // outstanding load, the asynchronous tile loads included.  With a list the fetch is issued
+    // for every tile (clamped into the list), so that exactly one load is younger than the tile
+    // loads an MFMA phase awaits.  Keys of a contiguous tile are plain arithmetic.
+    const bool has_list = nL > 0;
+    intx4 kidx[3] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    auto idx_fetch = [&](int t) -> intx4 {
+        const int c = min(max(t - nA, 0), nL - 1);
+        return *(const intx4*)(a.idx + lbase + (long long)c * TK + kq0);
     };
     // asynchronous: completion is awaited by wait_vmem()
     auto tile_load = [&](int t, char* Kb, char* Vb) {
@@ -151,12 +157,21 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
                                                          (int)((unsigned)min(t0 + j, sq.len - 1) * lstb + 16u * lch),
                                                          0, 0, 0);
         } else {
+            const intx4 key = idx_fetch(t);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(lrs, (lds_void*)(dst + j * lgrp), 16,
-                                                         (int)((unsigned)kidx[j] * lstb + 16u * lch), 0, 0, 0);
+                                                         (int)((unsigned)key[j] * lstb + 16u * lch), 0, 0, 0);
         }
     };
+
+    // In the main loop the loads are issued from inside the MFMA phase, which must stay one basic
+    // block: byte offsets of the wave's four rows without a branch (contiguous tile: scalar tile
+    // base + per-lane constants, clamped to the last row; list tile: index * stride).
+    unsigned lpre[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) lpre[j] = (unsigned)(kq0 + j) * lstb + 16u * lch;
+    const unsigned lmax = (unsigned)(sq.len - 1) * lstb + 16u * lch;
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane (n, hf) holds Q[row][16 ks + 8 hf .. +8)
     bf16x8 qf[8];
@@ -206,76 +221,108 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
     // a contiguous tile that starts beyond this wave's last row is hidden from all its rows (the
     // work-group still needs it for later rows): the wave computes nothing for it
     auto tile_on = [&](int t) -> bool { return wave_on && t < nT && !(t < nA && tile_start(t) > rw + 31); };
+    // 0: every (key, row) pair of the tile is visible; 1: contiguous tile that touches a region
+    // boundary or the diagonal; 2: last chunk of a list with padding entries
+    auto tile_mode = [&](int t) -> int {
+        if (t < nA) {
+            const int t0 = tile_start(t);
+            return ((t0 + TK - 1 <= rw) && (t0 + TK <= ninit || t0 >= W)) ? 0 : 1;
+        }
+        return (t == nT - 1 && (cnt & (TK - 1))) ? 2 : 0;
+    };
 
     floatx16 s[2];      // scores of the tile between its QK and its softmax phase
     bf16x8 pf[2][2];    // probabilities of the tile between its softmax and its PV phase
-    shortx8 vf[16];     // V^T operands of the tile, fetched during its softmax phase
-    bf16x8 kpre[2];     // first K operands of the next tile, fetched ahead of the PV MFMAs
 
-    // S^T = K Q^T : s[kb], 32 keys x 32 rows each.  Masks (tiles that touch a region boundary, the
-    // diagonal or a list tail) enter as the initial accumulator: 0 for a visible (key, row) pair,
-    // -inf otherwise; the common unmasked tile starts from literal 0.
-    auto qk_prefetch = [&](int t, const char* Kcur) {
-        if (!tile_on(t)) return;
-        const char* Kb = Kcur + koff;
+    // MFMA phase, one basic block: S^T = K Q^T of the next tile (s[kb]: 32 keys x 32 rows each),
+    // then O^T += V^T P^T of the current one, 32 MFMAs with their 48 LDS operand reads spread
+    // between them.  A wave gets a transposing read through only every ~24 cycles and a 16-byte
+    // read every ~14, so the reads of a tile take about as long as its MFMAs: the order below
+    // keeps both going (left alone, the compiler issues each read right before its MFMA and the
+    // phase waits out every LDS latency).  A tile this wave skips enters with pf = 0; scores of a
+    // skipped next tile are computed and ignored.
+    auto mfma_phase = [&](const char* Knext, const char* Vcur, char* Kld, char* Vld, int u, const intx4& keys) {
+        const char* Kb = Knext + koff;
+        const char* Vb = Vcur + voff;
+        // this wave's share of the loads of tile u (asynchronous; awaited by wait_vmem())
+        {
+            char* dst = (grpB ? Vld : Kld) + 4 * simd * lgrp;
+            const bool is_list = u >= nA;
+            const unsigned sbase = (unsigned)tile_start(u) * lstb;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) kpre[i] = *(const bf16x8*)(Kb + 512 * i);
-    };
-    auto qk = [&](int t, const char* Kcur) {
-        if (!tile_on(t)) return;
-        const char* Kb = Kcur + koff;
-        int mode = 0, t0 = 0;
-        if (t < nA) {
-            t0 = tile_start(t);
-            const bool interior = (t0 + TK - 1 <= rw) && (t0 + TK <= ninit || t0 >= W);
-            mode = interior ? 0 : 1;
-        } else if (t == nT - 1 && (cnt & (TK - 1))) {
-            mode = 2;
+            for (int j = 0; j < 4; ++j) {
+                const unsigned oc = min(sbase + lpre[j], lmax);
+                const unsigned ol = (unsigned)keys[j] * lstb + 16u * lch;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(lrs, (lds_void*)(dst + j * lgrp), 16,
+                                                         (int)(is_list ? ol : oc), 0, 0, 0);
+            }
         }
-        if (mode == 0) {
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kpre[kb], qf[0], kZero16, 0, 0, 0);
-        } else {
-            // key j = t0 + jl is visible to row r iff j <= r and (j < ninit or j >= W);
-            // entry jl of the last list chunk is real iff jl < rem
-            const int jr = mode == 1 ? r - t0 : cnt - (t - nA) * TK - 1;
-            const int jn = mode == 1 ? ninit - t0 : TK;
-            const int jw = W - t0;
+        for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                floatx16 bias;
+                const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb + 32 * ks);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? kZero16 : s[kb], 0, 0, 0);
+            }
+#pragma unroll
+        for (int sg = 0; sg < 4; ++sg)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                // keys 16 sg + 8 rd + 4 hf + (0..3) live in groups 8 rd + 4 hf + (0..3), row sg
+                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4*)(Vb + sg * 256 + 64 * db));
+                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) shortx4*)(Vb + 8 * VGRP + sg * 256 + 64 * db));
+                const shortx8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf[sg >> 1][sg & 1],
+                                                                 o[db], 0, 0, 0);
+            }
+        // program order of the reads: 16 K reads, then 32 V reads; the four tile loads come first
+        __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);              // K operands of QK 0..3
+#pragma unroll
+        for (int j = 0; j < 12; ++j) {                                  // QK 0..11: K read j + 4
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {                                   // QK 12..15: V reads 0..7
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 12; ++j) {                                  // PV 0..11: V reads 8..31
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);              // PV 12..15
+    };
+
+    // online softmax of this lane's query row (the other half of the row is 32 lanes away).
+    // In a masked tile key j = t0 + jl is visible to row r iff j <= r and (j < ninit or j >= W);
+    // entry jl of the last list chunk is real iff jl < rem; hidden scores count as -inf.  The
+    // hidden scores are overwritten in place before the common code.
+    auto softmax_phase = [&](int t) {
+        if (!tile_on(t)) {
+            const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+            pf[0][0] = zero8; pf[0][1] = zero8; pf[1][0] = zero8; pf[1][1] = zero8;
+            return;
+        }
+        const int mode = tile_mode(t);
+        if (mode != 0) {
+            const int t0 = mode == 1 ? tile_start(t) : 0;
+            const int jr = mode == 1 ? r - t0 : cnt - (t - nA) * TK - 1;
+            const int jn = mode == 1 ? ninit - t0 : TK;
+            const int jw = mode == 1 ? W - t0 : 0;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int jl = 32 * kb + 8 * (v >> 2) + 4 * hf + (v & 3);
                     const bool ok = (jl <= jr) & ((jl < jn) | (jl >= jw));
-                    bias[v] = ok ? 0.f : -INFINITY;
+                    s[kb][v] = ok ? s[kb][v] : -INFINITY;
                 }
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kpre[kb], qf[0], bias, 0, 0, 0);
-            }
         }
-#pragma unroll
-        for (int ks = 1; ks < 8; ++ks)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb + 32 * ks);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
-            }
-        // the remaining LDS operand reads run ahead of their MFMAs: six are issued up front (the
-        // two MFMAs on the prefetched operands cover part of their latency), then one per MFMA
-        // (left alone, the compiler issues each read right before its MFMA)
-        __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
-    };
-
-    // online softmax of this lane's query row (the other half of the row is 32 lanes away)
-    auto softmax = [&](int t, const char* Vcur) {
-        if (!tile_on(t)) return;
         float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
         for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, s[0][v]), s[1][v]);     // v_max3_f32
@@ -296,23 +343,6 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
                 for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         }
         const float mc = (mref == -INFINITY) ? 0.f : mref * c2;
-        // V^T operands of this tile for the coming MFMA phase.  A wave gets one transposing LDS read
-        // through about every 24 cycles, so the 32 reads of a tile cost more than its 16 PV MFMAs;
-        // issued here, spread between the exponentials, they cost nothing.
-        // keys 16 sg + 8 rd + 4 hf + (0..3) live in groups 8 rd + 4 hf + (0..3), row sg
-        {
-            const char* Vb = Vcur + voff;
-#pragma unroll
-            for (int sg = 0; sg < 4; ++sg)
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4*)(Vb + sg * 256 + 64 * db));
-                    const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) shortx4*)(Vb + 8 * VGRP + sg * 256 + 64 * db));
-                    vf[4 * sg + db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-        }
         float rs = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -326,71 +356,54 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
                 }
                 pf[kb][h8] = __builtin_convertvector(pv, bf16x8);
             }
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-        }
         l += rs;
     };
 
-    // O^T += V^T P^T
-    auto pv = [&](int t) {
-        if (!tile_on(t)) return;
-#pragma unroll
-        for (int sg = 0; sg < 4; ++sg)
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[4 * sg + db]),
-                                                                 pf[sg >> 1][sg & 1], o[db], 0, 0, 0);
-    };
-
-    // ---- prologue: tiles 0..2 (K by group A, V by group B), then the slot offset of group B
+    // ---- prologue: K tiles 0..2 (group A) / V tiles 0..1 (group B), then the slot offset of group B
+    const int la = grpB ? 2 : 3;                     // how many tiles ahead this wave loads
     if (nT > 0) {
-        idx_prefetch(0);
         tile_load(0, Ks0, Vs0);
-        if (nT > 1) {
-            idx_prefetch(1);
-            tile_load(1, Ks1, Vs1);
+        if (nT > 1) tile_load(1, Ks1, Vs1);
+        if (nT > 2 && !grpB) tile_load(2, Ks2, Vs2);
+        if (has_list) {
+            kidx[2] = idx_fetch(min(la - 1, nT - 1));    // for the first MFMA phase below
+            kidx[0] = idx_fetch(min(la, nT - 1));        // for the MFMA phase of tile 0
         }
-        if (nT > 2) {
-            idx_prefetch(2);
-            tile_load(2, Ks2, Vs2);
-        }
-        idx_prefetch(3);
+    }
+    {
+        const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+        pf[0][0] = zero8; pf[0][1] = zero8; pf[1][0] = zero8; pf[1][1] = zero8;
     }
     wait_vmem();
     slot_barrier();
-    if (!grpB) { qk_prefetch(0, Ks0); qk(0, Ks0); }
+    // scores of tile 0 (P = 0: O unchanged); its loads repeat tile la - 1 into its own stage
+    if (!grpB && nT > 0) mfma_phase(Ks0, Vs0, Ks2, Vs1, min(la - 1, nT - 1), kidx[2]);
     slot_barrier();
     if (grpB) {
-        qk_prefetch(0, Ks0);
-        qk(0, Ks0);
+        if (nT > 0) mfma_phase(Ks0, Vs0, Ks2, Vs1, min(la - 1, nT - 1), kidx[2]);
         slot_barrier();
     }
 
-    // one tile: softmax phase (which also fetches the tile's V operands), then MFMA phase.  The MFMA
-    // phase starts by awaiting the loads this wave issued at the start of its previous MFMA phase
-    // (they are published by the barrier that ends this phase) and issuing those of tile t + 3 into
-    // the stage tile t has left: its K was last read a slot ago, its V in the softmax phases.
-    auto tile_iter = [&](int t, char* Kcur, char* Vcur, const char* Knext) {
-        softmax(t, Vcur);
+    // one tile: softmax phase, then MFMA phase.  The MFMA phase starts by awaiting the loads this wave
+    // issued during its previous MFMA phase (the barrier that ends this phase publishes them); it
+    // issues those of tile t + 3 (K, group A: the stage tile t has left a slot ago) or t + 2 (V,
+    // group B: the stage tile t - 1 has left).  Past the end the last tile is loaded again into
+    // a stage nobody reads any more, which keeps the phase free of branches.
+    auto tile_iter = [&](int t, char* Kld, char* Vld, const char* Vcur, const char* Knext, intx4& keys,
+                         intx4& keys_next) {
+        softmax_phase(t);
+        if (has_list) keys_next = idx_fetch(min(t + 1 + la, nT - 1));   // for the MFMA phase after this one
         slot_barrier();
-        wait_vmem();
-        if (t + 3 < nT) {
-            tile_load(t + 3, Kcur, Vcur);
-            idx_prefetch(t + 4);
-        }
-        qk_prefetch(t + 1, Knext);
-        pv(t);
-        qk(t + 1, Knext);
+        // everything but the index fetch just issued, which is the youngest load
+        if (has_list) __builtin_amdgcn_s_waitcnt(0x0F71); else wait_vmem();
+        mfma_phase(Knext, Vcur, Kld, Vld, min(t + la, nT - 1), keys);
         slot_barrier();
     };
     // whole rounds of three tiles (one per LDS stage); tiles past the end only keep the barriers
     for (int t = 0; t < nT; t += 3) {
-        tile_iter(t, Ks0, Vs0, Ks1);
-        tile_iter(t + 1, Ks1, Vs1, Ks2);
-        tile_iter(t + 2, Ks2, Vs2, Ks0);
+        tile_iter(t, Ks0, Vs2, Vs0, Ks1, kidx[0], kidx[1]);
+        tile_iter(t + 1, Ks1, Vs0, Vs1, Ks2, kidx[1], kidx[2]);
+        tile_iter(t + 2, Ks2, Vs1, Vs2, Ks0, kidx[2], kidx[0]);
     }
     if (!grpB) slot_barrier();
 

@@ -63,6 +63,13 @@ def test_rejects_bad_params(api, kw, code):
     assert e.value.code == code
 
 
+def test_set_engine_accepts_only_known_modes(api):
+    for mode in (1, 2, 0):
+        api.anchor_set_engine(mode)
+    with pytest.raises(api.AnchorError):
+        api.anchor_set_engine(3)
+
+
 def test_null_pointers_and_workspace_are_rejected_on_host(api):
     p = _params(api)
     lib = ctypes.CDLL(api.LIB_PATH)

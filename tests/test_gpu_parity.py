@@ -21,6 +21,15 @@ def api():
     return _api
 
 
+@pytest.fixture(autouse=True, params=[0, 1, 2], ids=["engine-auto", "engine-128", "engine-256"])
+def engine_mode(request, api):
+    """Every test runs with the bf16 engine chosen per launch and with each of the two engines forced
+    (the 256-row engine falls back to the 128-row one where it does not apply)."""
+    api.anchor_set_engine(request.param)
+    yield request.param
+    api.anchor_set_engine(0)
+
+
 def _wl(name, dtype, lens, Hq, Hkv, d, block, seed, n_planted, mag=(2.5, 2.5), sink=4, q_shift=True, ar1=0.0):
     return synth.Workload(name, dtype, tuple(lens), Hq, Hkv, d, block, 0, 0, 1, 0.0, seed, n_planted=n_planted,
                           planted_mag=mag, sink_keys=sink, sink_mag=4.0, q_shift=q_shift, ar1=ar1)
