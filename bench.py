@@ -272,7 +272,8 @@ def main():
 
     N, d = wl.seqlens[0], wl.d
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "engine_bf16_stage3_%s_%s_traffic.txt" % (wl.name, args.signal))
+    tpath = os.path.join(ROOT, "profiles", "%s_stage3_%s_%s_traffic.txt" % (
+        main_res["stage3_kernel"].replace("_kernel", ""), wl.name, args.signal))
     if os.path.exists(tpath):
         for ln in open(tpath):
             if ln.startswith("traffic_bytes_per_launch="):
