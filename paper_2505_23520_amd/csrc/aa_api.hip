@@ -233,7 +233,7 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     sa.kp_f32 = (float*)(ws + pl.sel_kp);
     sa.is_bf16 = p->dtype == AA_BF16;
     sa.nwords = pl.nwords;
-    sa.keys_per_chunk = 2048;
+    sa.keys_per_chunk = kMaskChunkKeys * kMaskChunksPerWG;
     sa.counts = counts; sa.offsets = (long long*)offsets; sa.idx = idx;
     sa.idx_capacity = cap; sa.overflow = flag;
     sa.groups_total = pl.sz.groups;

@@ -4,6 +4,9 @@
 
 namespace aa {
 
+constexpr int kMaskChunkKeys = 1024;   // keys per chunk of the bf16 mask kernel (its LDS holds one chunk's compare words)
+constexpr int kMaskChunksPerWG = 1;    // consecutive chunks walked by one work-group (more was slower)
+
 struct SelectArgs {
     KParams p;
     const void *q, *k;
@@ -14,7 +17,7 @@ struct SelectArgs {
     int is_bf16;              // element type of q, k
     unsigned* bits;           // [groups][nwords] selection bit words, bit (j % 32) of word j / 32
     int nwords;               // ceil(N / 32)
-    int keys_per_chunk;       // bf16 mask kernel: keys handled by one work-group (multiple of 128)
+    int keys_per_chunk;       // bf16 mask kernel: keys per work-group, kMaskChunkKeys * kMaskChunksPerWG
     int* counts;
     long long* offsets;
     int* idx;

@@ -91,9 +91,21 @@ __global__ __launch_bounds__(128) void pool_q_fp32_kernel(SelectArgs a) {
 // C[key][row] = K qbar^T: keys are the M dimension, pooled rows the N dimension, so one lane owns
 // one pooled row and collects the compare bits of its row in registers.
 constexpr int kMaskTileKeys = 64;
+constexpr int kMaskChunkTiles = kMaskChunkKeys / kMaskTileKeys;   // tiles per work-group
 constexpr int kKGrp = 1024 + 16;                         // bytes per group of four K rows + pad
 constexpr int kKTile = 16 * kKGrp;
 typedef __attribute__((address_space(3))) void lds_void;
+
+namespace {
+// Work-group barrier that makes LDS writes visible but leaves vector-memory operations in flight
+// (__syncthreads() also waits for every outstanding load, the prefetched tiles included).
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_s_waitcnt(0xC07F);                  // lgkmcnt(0)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+}  // namespace
 
 __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     const KParams& p = a.p;
@@ -108,16 +120,17 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     const int g_last = (row_t0 + rows_here - 1) / p.step;
     const int Wmax = window_start(p, g_last);            // candidates of the tile end before Wmax
     const int key_lo = (p.n_init / kMaskTileKeys) * kMaskTileKeys;
-    const int chunk0 = key_lo + blockIdx.x * a.keys_per_chunk;
-    if (chunk0 >= Wmax) return;
-    const int chunk1 = min(chunk0 + a.keys_per_chunk, ((Wmax + kMaskTileKeys - 1) / kMaskTileKeys) * kMaskTileKeys);
-    const int ntiles = (chunk1 - chunk0) / kMaskTileKeys;
+    if (key_lo + (int)blockIdx.x * kMaskChunksPerWG * kMaskChunkKeys >= Wmax) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, hf = lane >> 5;
-    __shared__ __attribute__((aligned(16))) char ktile[2 * kKTile];
-    __shared__ unsigned rowword[2][128][2];
+    // one LDS object per stage: the compiler can then tell that the asynchronous loads into one stage
+    // do not alias the operand reads from another (with a single array it waits for the loads it
+    // has just issued before every tile's first read)
+    __shared__ __attribute__((aligned(16))) char kt0[kKTile], kt1[kKTile], kt2[kKTile];
+    // compare words of the whole chunk: [tile][pooled row][word]
+    __shared__ unsigned rowword[kMaskChunkTiles][128][2];
 
     // B operand: this lane's pooled query row, hi and lo parts, columns 16 ks + 8 hf .. +8
     bf16x8 bhi[8], blo[8];
@@ -144,12 +157,12 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
         (void*)kbase, 0, (int)((unsigned)(sq.len - 1) * kstb + 256u), 0x00020000);
     // loader: in the load of group gi lane l fetches the 16-byte chunk l % 16 of key 16 (l / 16) + gi
-    auto load_tile = [&](int t0, int buf) {
+    auto load_tile = [&](int t0, char* buf) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int gi = 4 * wave + j;
             const int key = min(t0 + 16 * (lane >> 4) + gi, sq.len - 1);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(ktile + buf * kKTile + gi * kKGrp), 16,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(krs, (lds_void*)(buf + gi * kKGrp), 16,
                                                      (int)((unsigned)key * kstb + 16u * (lane & 15)), 0, 0, 0);
         }
     };
@@ -157,14 +170,26 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     const int ngrp = (nblk + p.step - 1) / p.step;
     const int ngt = g_last - g_first + 1;
     // OR the rows of each group, clip to the group's candidate range, write the bit words of a tile
-    auto combine = [&](int t0, int par) {
-        for (int e = tid; e < ngt * 2; e += 256) {
-            const int gi = e >> 1, wi = e & 1;
+    // a work-group walks kMaskChunksPerWG chunks of kMaskChunkKeys keys: the pooled rows stay in
+    // registers, the compare words of a chunk are combined and written before the next one starts
+    const int koff = (n & 15) * kKGrp + (n >> 4) * 256 + 16 * hf;   // K row of key 32 kb + n
+    for (int cc = 0; cc < kMaskChunksPerWG; ++cc) {
+    const int chunk0 = key_lo + ((int)blockIdx.x * kMaskChunksPerWG + cc) * kMaskChunkKeys;
+    if (chunk0 >= Wmax) break;
+    const int chunk1 = min(chunk0 + kMaskChunkKeys, ((Wmax + kMaskTileKeys - 1) / kMaskTileKeys) * kMaskTileKeys);
+    const int ntiles = (chunk1 - chunk0) / kMaskTileKeys;
+    // After the tile loop: OR the rows of each group, clip to the group's candidate range, write the
+    // bit words of the chunk.  (This stays outside the tile loop: before an inner loop that reads
+    // LDS, and before an LDS atomic, the compiler waits for every outstanding asynchronous load
+    // into LDS, which would serialise the tile loads with the arithmetic.)
+    auto combine_all = [&]() {
+        for (int e = tid; e < ngt * 2 * ntiles; e += 256) {
+            const int wi = e & 1, gi = (e >> 1) % ngt, tl = (e >> 1) / ngt;
             const int g = g_first + gi;
             const int lr0 = g * p.step - row_t0;
             unsigned wd = 0;
-            for (int s = 0; s < p.step && lr0 + s < rows_here; ++s) wd |= rowword[par][lr0 + s][wi];
-            const int j0 = t0 + 32 * wi;
+            for (int s = 0; s < p.step && lr0 + s < rows_here; ++s) wd |= rowword[tl][lr0 + s][wi];
+            const int j0 = chunk0 + tl * kMaskTileKeys + 32 * wi;
             const int Wg = window_start(p, g);
             const int lo = max(p.n_init - j0, 0), hi = min(Wg - j0, 32);   // keep n_init <= j0 + bit < Wg
             unsigned keep = 0;
@@ -174,23 +199,35 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
         }
     };
 
-    load_tile(chunk0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
-    __syncthreads();
-    const int koff = (n & 15) * kKGrp + (n >> 4) * 256 + 16 * hf;   // K row of key 32 kb + n
-    for (int t = 0; t < ntiles; ++t) {
+    // three stages: the loads of tile t + 2 are issued at the start of tile t and awaited at the end
+    // of tile t + 1 (one tile of arithmetic is shorter than the load latency)
+    load_tile(chunk0, kt0);
+    if (ntiles > 1) load_tile(chunk0 + kMaskTileKeys, kt1);
+    if (ntiles > 1) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F70);   // tile 0 is there
+    lds_barrier();
+    auto tile_step = [&](int t, const char* Kcur, char* Kld) {
         const int t0 = chunk0 + t * kMaskTileKeys;
-        if (t + 1 < ntiles) load_tile(t0 + kMaskTileKeys, (t + 1) & 1);
-        const char* Kb = ktile + (t & 1) * kKTile + koff;
+        if (t + 2 < ntiles) load_tile(t0 + 2 * kMaskTileKeys, Kld);
+        const char* Kb = Kcur + koff;
         floatx16 c[2];
+        // the two accumulators alternate, so no MFMA waits for the one issued just before it
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 kf0 = *(const bf16x8*)(Kb + 32 * ks);
+            const bf16x8 kf1 = *(const bf16x8*)(Kb + 512 + 32 * ks);
+            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, blo[ks], ks == 0 ? kZero16 : c[0], 0, 0, 0);
+            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, blo[ks], ks == 0 ? kZero16 : c[1], 0, 0, 0);
+            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, bhi[ks], c[0], 0, 0, 0);
+            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, bhi[ks], c[1], 0, 0, 0);
+        }
+        // operand reads run ahead of their MFMAs
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb + 32 * ks);
-                c[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, blo[ks], ks == 0 ? kZero16 : c[kb], 0, 0, 0);
-                c[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, bhi[ks], c[kb], 0, 0, 0);
-            }
+        for (int i = 0; i < 6; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         // threshold compare; the lane gathers the bits of its 16 keys per 32-key block, the
         // other half of the wave holds the remaining 16
 #pragma unroll
@@ -203,13 +240,25 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
             }
             wd <<= 4 * hf;
             wd |= (unsigned)__shfl_xor((int)wd, 32, 64);
-            if (hf == 0) rowword[t & 1][lr][kb] = wd;
+            if (hf == 0) rowword[t][lr][kb] = wd;
         }
-        if (t > 0) combine(t0 - kMaskTileKeys, (t - 1) & 1);
-        __builtin_amdgcn_s_waitcnt(0x0F70);              // next tile has landed
-        __syncthreads();
+        // tile t + 1 has landed: everything but the four loads of tile t + 2 just issued
+        if (t + 2 < ntiles) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F70);
+        lds_barrier();
+    };
+    // fully unrolled (at most kMaskChunkTiles tiles, forward branches only): with loads left in
+    // flight across a loop's back edge the compiler falls back to waiting for all of them at the
+    // loop header
+    static_assert(kMaskChunkTiles == 16, "tile loop below is written out for 16 tiles");
+#pragma unroll
+    for (int t3 = 0; t3 < 18; t3 += 3) {
+        if (t3 < ntiles) tile_step(t3, kt0, kt2);
+        if (t3 + 1 < ntiles) tile_step(t3 + 1, kt1, kt0);
+        if (t3 + 2 < ntiles) tile_step(t3 + 2, kt2, kt1);
     }
-    combine(chunk0 + (ntiles - 1) * kMaskTileKeys, (ntiles - 1) & 1);
+    combine_all();
+    __syncthreads();                                 // rowword is reused by the next chunk
+    }
 }
 
 // ------------------------------------------------------------------ mask, fp32 vector FMA
