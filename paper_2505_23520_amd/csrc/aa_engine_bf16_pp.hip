@@ -5,10 +5,10 @@
 //   work-group = two consecutive query blocks of one head = 8 waves x 32 query rows, one
 //   work-group per CU.  Waves w and w + 4 share a SIMD; waves 0-3 form group A, waves 4-7
 //   group B.  Time is cut into slots by work-group barriers.  In every slot one group runs its
-//   MFMA phase (S^T = K Q^T of tile t + 1, then O^T += V^T P^T of tile t: 32 MFMAs interleaved
-//   with their LDS operand reads) while the other runs its softmax phase (row max, exp2, row
-//   sum, bf16 conversion of tile t on the vector ALU, and the issue of this wave's share of the
-//   tile loads); then they swap.  Group B runs one slot behind group A.
+//   MFMA phase (this wave's share of the tile loads, S^T = K Q^T of tile t + 1, then
+//   O^T += V^T P^T of tile t: 32 MFMAs interleaved with their LDS operand reads) while the other
+//   runs its softmax phase (masks, row max, exp2, row sum, bf16 conversion of tile t: vector ALU
+//   only); then they swap.  Group B runs one slot behind group A.
 //   K/V tiles are triple-buffered in LDS and shared by the 256 rows.  Group A's waves issue the
 //   direct-to-LDS loads of the K tiles (three tiles ahead), group B's those of the V tiles (two
 //   tiles ahead), from inside their MFMA phase, and wait for them at the start of their next
