@@ -250,7 +250,7 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
         else
             hipLaunchKernelGGL(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);
         AA_LAUNCHED("pool_q kernel");
-        hipLaunchKernelGGL(pool_k_kernel, dim3(kp.nblk_max, kp.Hkv, kp.B), dim3(128), 0, st, sa);
+        hipLaunchKernelGGL(pool_k_kernel, dim3(kp.nblk_max, kp.Hkv, kp.B), dim3(256), 0, st, sa);
         AA_LAUNCHED("pool_k_kernel");
         static bool attr_set_blk = false;
         if (!attr_set_blk) {

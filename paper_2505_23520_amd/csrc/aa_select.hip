@@ -302,8 +302,9 @@ __global__ __launch_bounds__(256) void mask_fp32_kernel(SelectArgs a) {
 // the difference test of Sec. 3.2 on the block's average key.  Tiny next to the stripe mask
 // (pooled rows x pooled keys), so plain fp32 FMAs.
 
-// kbar_J = mean of key block J.  grid (nblk_max, Hkv, B), 128 threads: one column per thread.
-__global__ __launch_bounds__(128) void pool_k_kernel(SelectArgs a) {
+// kbar_J = mean of key block J.  grid (nblk_max, Hkv, B), 256 threads.  bf16 (d = 128): thread
+// (c, rs) sums the 16-byte chunk c of rows rs, rs + 16, ...; fp32: one column per thread.
+__global__ __launch_bounds__(256) void pool_k_kernel(SelectArgs a) {
     const KParams& p = a.p;
     const int J = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
     const Seq sq = seq_of(p, b);
@@ -312,16 +313,36 @@ __global__ __launch_bounds__(128) void pool_k_kernel(SelectArgs a) {
     const int r1 = min(r0 + p.bq, sq.len);
     const long long kb = (p.packed ? (long long)hk * p.blk_cap + sq.blk0 : ((long long)b * p.Hkv + hk) * p.blk_cap) + J;
     const long long base = tok_offset(p, p.ks, sq, b, hk, 0);
-    for (int c = threadIdx.x; c < p.d; c += blockDim.x) {
-        float s = 0.f;
-        if (a.is_bf16) {
-            const unsigned short* src = (const unsigned short*)a.k + base + c;
-            for (int r = r0; r < r1; ++r) s += bf16_to_f(src[(long long)r * p.ks[2]]);
-        } else {
-            const float* src = (const float*)a.k + base + c;
-            for (int r = r0; r < r1; ++r) s += src[(long long)r * p.ks[2]];
+    const int tid = threadIdx.x;
+    if (a.is_bf16) {
+        const int c = tid & 15, rs = tid >> 4;
+        const unsigned short* src = (const unsigned short*)a.k + base + 8 * c;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int r = r0 + rs; r < r1; r += 16) {
+            const uintx4 x = *(const uintx4*)(src + (long long)r * p.ks[2]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] += __uint_as_float(x[e] << 16);
+                acc[2 * e + 1] += __uint_as_float(x[e] & 0xffff0000u);
+            }
         }
-        a.kp_f32[kb * p.d + c] = s / (float)(r1 - r0);
+        __shared__ float red[16][128];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[rs][8 * c + e] = acc[e];
+        __syncthreads();
+        if (tid < 128) {
+            float s0 = 0.f;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) s0 += red[k][tid];
+            a.kp_f32[kb * 128 + tid] = s0 / (float)(r1 - r0);
+        }
+    } else {
+        const float* src = (const float*)a.k + base;
+        for (int c = tid; c < p.d; c += 256) {
+            float s0 = 0.f;
+            for (int r = r0; r < r1; ++r) s0 += src[(long long)r * p.ks[2] + c];
+            a.kp_f32[kb * p.d + c] = s0 / (float)(r1 - r0);
+        }
     }
 }
 
