@@ -217,6 +217,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = synth.workloads()[args.workload]
+    if wl.packed or wl.dtype != "bf16":
+        sys.exit("bench.py times the single-sequence bf16 workloads (gqa_8k, gqa_32k, gqa_128k); "
+                 "the packed and fp32 workloads are parity-test cases")
     log = lambda s: print("[bench] " + s, file=sys.stderr, flush=True)
 
     if args.theta_sweep:
