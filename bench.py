@@ -16,6 +16,10 @@ resident in HBM.  One JSON line is printed:
   calibrated          : the same measurements with the planted magnitudes in scaled-logit
                         units (signal="logit"), the regime where the threshold separates
                         stripes from background
+  peaked              : the same with the planted magnitudes times three and the threshold
+                        scaled with them (signal="peaked"): the planted columns then hold most
+                        of a row's attention mass, as in real heads, so high sparsity and high
+                        recall occur together
   cpu_baseline        : the fp64 CPU oracle timed on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -201,7 +205,7 @@ def main():
     ap.add_argument("--step", type=int, default=16, help="query blocks sharing one list (paper default 16)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-calibrated", action="store_true")
-    ap.add_argument("--signal", default="literal", choices=["literal", "logit"])
+    ap.add_argument("--signal", default="literal", choices=["literal", "logit", "peaked"])
     ap.add_argument("--granularity", default="stripe", choices=["stripe", "block"],
                     help="with --theta-sweep: identification per key column (the method) or per key block")
     ap.add_argument("--theta-sweep", default=None, metavar="T1,T2,...",
@@ -232,9 +236,14 @@ def main():
     main_res, tensors = measure(api, torch, synth, wl, args.signal, args.step, args.steps, args.warmup, log=log)
     del tensors
     torch.cuda.empty_cache()
-    calibrated = None
+    calibrated, peaked = None, None
     if not args.no_calibrated and args.signal == "literal":
         calibrated, t2 = measure(api, torch, synth, wl, "logit", args.step, args.steps, args.warmup, log=log)
+        del t2
+        torch.cuda.empty_cache()
+        # planted magnitudes times three, threshold scaled with them
+        peaked, t2 = measure(api, torch, synth, wl, "peaked", args.step, args.steps, args.warmup,
+                             theta=3.0 * wl.theta, log=log)
         del t2
         torch.cuda.empty_cache()
 
@@ -304,6 +313,7 @@ def main():
                      "frac_of_sustained_mfma": flops3 / s3 / mfma_sustained if flops3 else 0.0,
                      "sustained_copy_TBps_this_gpu": hbm_sustained / 1e12},
         "calibrated": calibrated,
+        "peaked": peaked,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

@@ -17,6 +17,12 @@ direction per KV head.
   * "logit":   keys get m * d**0.25 * u and queries d**0.25 * u, so the scaled
     logit q.k/sqrt(d) moves by m.  This is the regime in which the threshold
     separates stripes from background (the paper's 89-97 % sparsity range).
+  * "peaked":  as "logit" with every planted magnitude (stripes and sink) times
+    three.  With i.i.d. Gaussian background keys a 128k-token row spreads about
+    N * e^(1/2) of softmax mass over ordinary columns; only at these magnitudes
+    do the planted columns hold most of a row's mass, as the stripes and sinks
+    of real heads do (Section 2.2), so that recall near one and high sparsity
+    can occur together.
 """
 from __future__ import annotations
 
@@ -99,12 +105,13 @@ def make_sequence(wl: Workload, seq: int, N: int | None = None, signal: str = "l
     has its own random stream.  ``N`` overrides the length (shorter parity cases
     of the same recipe).  Values are bf16-representable when wl.dtype == "bf16".
     """
-    if signal not in ("literal", "logit"):
-        raise ValueError("signal must be 'literal' or 'logit'")
+    if signal not in ("literal", "logit", "peaked"):
+        raise ValueError("signal must be 'literal', 'logit' or 'peaked'")
     N = int(wl.seqlens[seq] if N is None else N)
     d, grp = wl.d, wl.Hq // wl.Hkv
     hk_list = list(range(wl.Hkv)) if heads_kv is None else list(heads_kv)
-    amp = float(d) ** 0.25 if signal == "logit" else 1.0
+    amp = 1.0 if signal == "literal" else float(d) ** 0.25
+    gain = 3.0 if signal == "peaked" else 1.0       # on the planted magnitudes
     Q = np.empty((len(hk_list) * grp, N, d), np.float32)
     K = np.empty((len(hk_list), N, d), np.float32)
     V = np.empty((len(hk_list), N, d), np.float32)
@@ -119,9 +126,9 @@ def make_sequence(wl: Workload, seq: int, N: int | None = None, signal: str = "l
         lo, hi = wl.planted_mag
         mags = rng.uniform(lo, hi, size=cols.size) if hi > lo else np.full(cols.size, lo)
         if cols.size:
-            k[cols] += (amp * mags[:, None] * u[None, :]).astype(np.float32)
+            k[cols] += (amp * gain * mags[:, None] * u[None, :]).astype(np.float32)
         if wl.sink_keys:
-            k[: wl.sink_keys] += (amp * wl.sink_mag * u).astype(np.float32)
+            k[: wl.sink_keys] += (amp * gain * wl.sink_mag * u).astype(np.float32)
         planted.append((cols, mags))
         for t in range(grp):
             qh = rng.standard_normal((N, d), dtype=np.float32)

@@ -64,11 +64,14 @@ def test_gqa_32k_theta_sweep(api):
         torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("signal", ["literal", "logit"])
+@pytest.mark.parametrize("signal", ["literal", "logit", "peaked"])
 def test_gqa_128k_sampled(api, signal):
     wl = synth.workloads()["gqa_128k"]
     samples = [(0, 0, 0), (0, 7, 1), (0, 13, 20), (0, 26, 41), (0, 31, 63)]
-    run, worst, stats = _run(api, wl, _cfg(api, wl), signal, samples)
+    theta = 3.0 * wl.theta if signal == "peaked" else wl.theta     # as bench.py runs it
+    run, worst, stats = _run(api, wl, _cfg(api, wl, theta=theta), signal, samples)
+    if signal == "peaked":      # the planted columns before a group's window are kept, little else
+        assert 0 < worst["selected"] < 0.05 * worst["candidates"]
     N, Hq = wl.seqlens[0], wl.Hq
     assert 0 < stats[0] <= Hq * N * (N + 1) // 2
     del run
