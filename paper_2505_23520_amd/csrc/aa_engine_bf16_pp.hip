@@ -359,6 +359,16 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
         l += rs;
     };
 
+    // ---- The MFMA phase always runs, also for a tile this wave skips (P = 0) and for the padding
+    // tiles of the last round, and 0 x V must then be 0: no V stage may hold leftovers of another
+    // kernel that decode as Inf or NaN.  Clear them before the first loads.
+    {
+        const intx4 z = {0, 0, 0, 0};
+        for (int e = tid; e < VBYTES / 16; e += 512) {
+            *(intx4*)(Vs0 + 16 * e) = z; *(intx4*)(Vs1 + 16 * e) = z; *(intx4*)(Vs2 + 16 * e) = z;
+        }
+        __syncthreads();
+    }
     // ---- prologue: K tiles 0..2 (group A) / V tiles 0..1 (group B), then the slot offset of group B
     const int la = grpB ? 2 : 3;                     // how many tiles ahead this wave loads
     if (nT > 0) {
