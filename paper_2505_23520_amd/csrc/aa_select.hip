@@ -149,8 +149,8 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
             blo[ks] = rok ? y : zero8;
         }
     }
-    // pooled anchor of the lane's row; NaN = no such row (never selects)
-    const float xb = rok ? (p.use_anchor ? a.xa[bi] : 0.f) : __builtin_nanf("");
+    // theta minus the pooled anchor of the lane's row; -inf = no such row (never selects)
+    const float toff = rok ? p.theta - (p.use_anchor ? a.xa[bi] : 0.f) : -INFINITY;
 
     const unsigned short* kbase = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, b, hk, 0);
     const unsigned kstb = (unsigned)p.ks[2] * 2u;
@@ -228,19 +228,21 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-        // threshold compare; the lane gathers the bits of its 16 keys per 32-key block, the
-        // other half of the wave holds the remaining 16
+        // Threshold test xbar - sigma s <= theta as the sign of sigma s + (theta - xbar): two
+        // instructions per score (fma, then the sign bit is shifted into a word), no compare / select
+        // chains.  The lane gathers the bits of its 16 keys per 32-key block (accumulator register v
+        // holds key 8 (v / 4) + 4 hf + v % 4), the other half of the wave holds the remaining 16.
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-            unsigned wd = 0;
+            unsigned neg = 0;                        // bit v = sign of score v's margin
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const bool pred = (xb - p.sigma * c[kb][v]) <= p.theta;
-                wd |= pred ? (1u << (8 * (v >> 2) + (v & 3))) : 0u;
-            }
+            for (int v = 15; v >= 0; --v)
+                neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(fmaf(p.sigma, c[kb][v], toff)), 31);
+            const unsigned sel = ~neg & 0xffffu;
+            unsigned wd = (sel & 0xfu) | ((sel & 0xf0u) << 4) | ((sel & 0xf00u) << 8) | ((sel & 0xf000u) << 12);
             wd <<= 4 * hf;
-            wd |= (unsigned)__shfl_xor((int)wd, 32, 64);
-            if (hf == 0) rowword[t][lr][kb] = wd;
+            const auto both = __builtin_amdgcn_permlane32_swap(wd, wd, false, false);
+            if (hf == 0) rowword[t][lr][kb] = both[0] | both[1];
         }
         // tile t + 1 has landed: everything but the four loads of tile t + 2 just issued
         if (t + 2 < ntiles) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F70);
