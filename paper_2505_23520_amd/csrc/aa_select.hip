@@ -201,13 +201,16 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
 
     // three stages: the loads of tile t + 2 are issued at the start of tile t and awaited at the end
     // of tile t + 1 (one tile of arithmetic is shorter than the load latency)
+    // Every tile issues exactly four loads and every wait is vmcnt(4), unconditionally (past the
+    // chunk's end the last tile is fetched again into a stage nobody reads any more): with loads or
+    // waits under conditions the compiler has to assume paths on which a stage's loads are still
+    // pending when it is read, and guards every third tile with a wait for all loads.
     load_tile(chunk0, kt0);
-    if (ntiles > 1) load_tile(chunk0 + kMaskTileKeys, kt1);
-    if (ntiles > 1) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F70);   // tile 0 is there
+    load_tile(chunk0 + min(1, ntiles - 1) * kMaskTileKeys, kt1);
+    __builtin_amdgcn_s_waitcnt(0x0F74);              // tile 0 is there
     lds_barrier();
     auto tile_step = [&](int t, const char* Kcur, char* Kld) {
-        const int t0 = chunk0 + t * kMaskTileKeys;
-        if (t + 2 < ntiles) load_tile(t0 + 2 * kMaskTileKeys, Kld);
+        load_tile(chunk0 + min(t + 2, ntiles - 1) * kMaskTileKeys, Kld);
         const char* Kb = Kcur + koff;
         floatx16 c[2];
         // the two accumulators alternate, so no MFMA waits for the one issued just before it
@@ -245,7 +248,7 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
             if (hf == 0) rowword[t][lr][kb] = both[0] | both[1];
         }
         // tile t + 1 has landed: everything but the four loads of tile t + 2 just issued
-        if (t + 2 < ntiles) __builtin_amdgcn_s_waitcnt(0x0F74); else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_s_waitcnt(0x0F74);
         lds_barrier();
     };
     // fully unrolled (at most kMaskChunkTiles tiles, forward branches only): with loads left in
@@ -254,10 +257,14 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     static_assert(kMaskChunkTiles == 16, "tile loop below is written out for 16 tiles");
 #pragma unroll
     for (int t3 = 0; t3 < 18; t3 += 3) {
-        if (t3 < ntiles) tile_step(t3, kt0, kt2);
-        if (t3 + 1 < ntiles) tile_step(t3 + 1, kt1, kt0);
-        if (t3 + 2 < ntiles) tile_step(t3 + 2, kt2, kt1);
+        if (t3 >= ntiles) break;
+        tile_step(t3, kt0, kt2);
+        if (t3 + 1 >= ntiles) break;
+        tile_step(t3 + 1, kt1, kt0);
+        if (t3 + 2 >= ntiles) break;
+        tile_step(t3 + 2, kt2, kt1);
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // the trailing loads have landed before LDS is reused
     combine_all();
     __syncthreads();                                 // rowword is reused by the next chunk
     }
