@@ -265,9 +265,10 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     } else if (p->dtype == AA_BF16) {
         hipLaunchKernelGGL(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
         AA_LAUNCHED("pool_q_bf16_kernel");
-        const int RT = 128 - 128 % kp.step;
-        const dim3 gm((unsigned)cdiv(kp.N, sa.keys_per_chunk), (unsigned)cdiv(kp.nblk_max, RT),
-                      (unsigned)(kp.B * kp.Hq));
+        // row tiles are folded in pairs (short with long); the longest sequence bounds every other
+        const int ny = (int)cdiv(kp.nblk_max, mask_row_tile(kp.step));
+        const dim3 gm((unsigned)mask_grid_x(kp.nblk_max, kp.step, kp.bq, kp.w, kp.n_init),
+                      (unsigned)((ny + 1) / 2), (unsigned)(kp.B * kp.Hq));
         hipLaunchKernelGGL(mask_bf16_kernel, gm, dim3(256), 0, st, sa);
         AA_LAUNCHED("mask_bf16_kernel");
     } else {

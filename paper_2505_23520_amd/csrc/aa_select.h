@@ -7,6 +7,37 @@ namespace aa {
 constexpr int kMaskChunkKeys = 1024;   // keys per chunk of the bf16 mask kernel (its LDS holds one chunk's compare words)
 constexpr int kMaskChunksPerWG = 1;    // consecutive chunks walked by one work-group (more was slower)
 
+// bf16 mask kernel: pooled rows per row tile, and the number of key chunks a row tile has
+// candidates in (all groups of the tile end their candidates before the last group's window).
+// Host and device use the same arithmetic: the host sizes the grid with it, the kernel decodes
+// its work-group index with it.
+__host__ __device__ inline int mask_row_tile(int step) { return 128 - 128 % step; }
+__host__ __device__ inline int mask_tile_chunks(int nblk, int rt, int step, int bq, int w, int n_init) {
+    const int RT = mask_row_tile(step);
+    if (rt < 0 || rt * RT >= nblk) return 0;
+    const int rows = nblk - rt * RT < RT ? nblk - rt * RT : RT;
+    const int g_last = (rt * RT + rows - 1) / step;
+    const long long W = (long long)g_last * step * bq - w;
+    const int Wmax = W > n_init ? (int)W : n_init;
+    const int key_lo = (n_init / 64) * 64;
+    const int span = kMaskChunkKeys * kMaskChunksPerWG;
+    return Wmax > key_lo ? (Wmax - key_lo + span - 1) / span : 0;
+}
+// Grid width: row tiles y and ny - 1 - y share one grid row (causal fold: a short and a long tile
+// together have about the same number of chunks everywhere), so nearly every work-group has work.
+__host__ __device__ inline int mask_grid_x(int nblk, int step, int bq, int w, int n_init) {
+    const int RT = mask_row_tile(step);
+    const int ny = (nblk + RT - 1) / RT;
+    int gx = 1;
+    for (int y = 0; 2 * y < ny; ++y) {
+        const int m = ny - 1 - y;
+        const int n = mask_tile_chunks(nblk, y, step, bq, w, n_init) +
+                      (m != y ? mask_tile_chunks(nblk, m, step, bq, w, n_init) : 0);
+        gx = n > gx ? n : gx;
+    }
+    return gx;
+}
+
 struct SelectArgs {
     KParams p;
     const void *q, *k;

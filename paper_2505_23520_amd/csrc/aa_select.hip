@@ -84,10 +84,11 @@ __global__ __launch_bounds__(128) void pool_q_fp32_kernel(SelectArgs a) {
 }
 
 // ------------------------------------------------------------------ mask, bf16 MFMA
-// grid (key chunks, row tiles, B*Hq), 256 threads = 4 waves, two work-groups per CU.
+// grid (key chunks of a folded pair of row tiles, pairs of row tiles, B*Hq), 256 threads = 4 waves,
+// three work-groups per CU.
 // A row tile holds RT = 128 - 128 % step pooled rows, so no group straddles two tiles; wave w owns
 // its rows 32 w .. 32 w + 31.  The chunk's keys pass through LDS in 64-key tiles (16-byte
-// direct-to-LDS loads, double-buffered, same padded group layout as the attention engine).
+// direct-to-LDS loads, two stages, same padded group layout as the attention engine).
 // C[key][row] = K qbar^T: keys are the M dimension, pooled rows the N dimension, so one lane owns
 // one pooled row and collects the compare bits of its row in registers.
 constexpr int kMaskTileKeys = 64;
@@ -107,20 +108,31 @@ __device__ __forceinline__ void lds_barrier() {
 }
 }  // namespace
 
-__global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
+__global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
     const KParams& p = a.p;
     const int b = blockIdx.z / p.Hq, h = blockIdx.z % p.Hq, hk = h / p.grp;
     const Seq sq = seq_of(p, b);
     const int nblk = (sq.len + p.bq - 1) / p.bq;
-    const int RT = 128 - 128 % p.step;
-    const int row_t0 = blockIdx.y * RT;                  // first pooled row (query block) of the tile
+    const int RT = mask_row_tile(p.step);
+    // Grid row y serves row tile y with its first work-groups and row tile ny - 1 - y, chunks counted
+    // from the grid row's far end, with the rest.
+    const int ny = (nblk + RT - 1) / RT;
+    int rt = blockIdx.y, chunk = blockIdx.x;
+    if (2 * rt >= ny) return;
+    if (chunk >= mask_tile_chunks(nblk, rt, p.step, p.bq, p.w, p.n_init)) {
+        const int m = ny - 1 - rt;
+        chunk = (int)gridDim.x - 1 - (int)blockIdx.x;
+        if (m == rt || chunk >= mask_tile_chunks(nblk, m, p.step, p.bq, p.w, p.n_init)) return;
+        rt = m;
+    }
+    const int row_t0 = rt * RT;                          // first pooled row (query block) of the tile
     if (row_t0 >= nblk) return;
     const int rows_here = min(RT, nblk - row_t0);
     const int g_first = row_t0 / p.step;
     const int g_last = (row_t0 + rows_here - 1) / p.step;
     const int Wmax = window_start(p, g_last);            // candidates of the tile end before Wmax
     const int key_lo = (p.n_init / kMaskTileKeys) * kMaskTileKeys;
-    if (key_lo + (int)blockIdx.x * kMaskChunksPerWG * kMaskChunkKeys >= Wmax) return;
+    if (key_lo + chunk * kMaskChunksPerWG * kMaskChunkKeys >= Wmax) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -128,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     // one LDS object per stage: the compiler can then tell that the asynchronous loads into one stage
     // do not alias the operand reads from another (with a single array it waits for the loads it
     // has just issued before every tile's first read)
-    __shared__ __attribute__((aligned(16))) char kt0[kKTile], kt1[kKTile], kt2[kKTile];
+    __shared__ __attribute__((aligned(16))) char kt0[kKTile], kt1[kKTile];
     // compare words of the whole chunk: [tile][pooled row][word]
     __shared__ unsigned rowword[kMaskChunkTiles][128][2];
 
@@ -174,7 +186,7 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     // registers, the compare words of a chunk are combined and written before the next one starts
     const int koff = (n & 15) * kKGrp + (n >> 4) * 256 + 16 * hf;   // K row of key 32 kb + n
     for (int cc = 0; cc < kMaskChunksPerWG; ++cc) {
-    const int chunk0 = key_lo + ((int)blockIdx.x * kMaskChunksPerWG + cc) * kMaskChunkKeys;
+    const int chunk0 = key_lo + (chunk * kMaskChunksPerWG + cc) * kMaskChunkKeys;
     if (chunk0 >= Wmax) break;
     const int chunk1 = min(chunk0 + kMaskChunkKeys, ((Wmax + kMaskTileKeys - 1) / kMaskTileKeys) * kMaskTileKeys);
     const int ntiles = (chunk1 - chunk0) / kMaskTileKeys;
@@ -183,12 +195,20 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
     // LDS, and before an LDS atomic, the compiler waits for every outstanding asynchronous load
     // into LDS, which would serialise the tile loads with the arithmetic.)
     auto combine_all = [&]() {
+        // consecutive threads take consecutive words of one group (coalesced stores); each starts
+        // its walk over the group's rows at a different row, which spreads a wave's LDS reads over
+        // the banks (from the same row they would be 16 reads to one bank)
         for (int e = tid; e < ngt * 2 * ntiles; e += 256) {
-            const int wi = e & 1, gi = (e >> 1) % ngt, tl = (e >> 1) / ngt;
+            const int wi = e & 1, tl = (e >> 1) % ntiles, gi = (e >> 1) / ntiles;
             const int g = g_first + gi;
             const int lr0 = g * p.step - row_t0;
+            const int nr = min(p.step, rows_here - lr0);
             unsigned wd = 0;
-            for (int s = 0; s < p.step && lr0 + s < rows_here; ++s) wd |= rowword[tl][lr0 + s][wi];
+            int s = tl % nr;
+            for (int c = 0; c < nr; ++c) {
+                wd |= rowword[tl][lr0 + s][wi];
+                s = s + 1 == nr ? 0 : s + 1;
+            }
             const int j0 = chunk0 + tl * kMaskTileKeys + 32 * wi;
             const int Wg = window_start(p, g);
             const int lo = max(p.n_init - j0, 0), hi = min(Wg - j0, 32);   // keep n_init <= j0 + bit < Wg
@@ -199,18 +219,17 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
         }
     };
 
-    // three stages: the loads of tile t + 2 are issued at the start of tile t and awaited at the end
-    // of tile t + 1 (one tile of arithmetic is shorter than the load latency)
-    // Every tile issues exactly four loads and every wait is vmcnt(4), unconditionally (past the
-    // chunk's end the last tile is fetched again into a stage nobody reads any more): with loads or
-    // waits under conditions the compiler has to assume paths on which a stage's loads are still
-    // pending when it is read, and guards every third tile with a wait for all loads.
+    // two stages: the loads of tile t + 1 are issued at the start of tile t and awaited at its end.
+    // (Three stages with a two-tile lead were 12 % slower: 50 KB of LDS per work-group leave room for
+    // three work-groups per CU, 66 KB only for two, and the third hides both the load latency and
+    // the 4 us a CU needs to replace a finished work-group.)  Every tile issues its four loads
+    // unconditionally (past the chunk's end the last tile is fetched again into the stage nobody
+    // reads any more), so no statically possible path reads a stage whose loads might be pending.
     load_tile(chunk0, kt0);
-    load_tile(chunk0 + min(1, ntiles - 1) * kMaskTileKeys, kt1);
-    __builtin_amdgcn_s_waitcnt(0x0F74);              // tile 0 is there
+    __builtin_amdgcn_s_waitcnt(0x0F70);              // tile 0 is there
     lds_barrier();
     auto tile_step = [&](int t, const char* Kcur, char* Kld) {
-        load_tile(chunk0 + min(t + 2, ntiles - 1) * kMaskTileKeys, Kld);
+        load_tile(chunk0 + min(t + 1, ntiles - 1) * kMaskTileKeys, Kld);
         const char* Kb = Kcur + koff;
         floatx16 c[2];
         // the two accumulators alternate, so no MFMA waits for the one issued just before it
@@ -247,22 +266,16 @@ __global__ __launch_bounds__(256, 2) void mask_bf16_kernel(SelectArgs a) {
             const auto both = __builtin_amdgcn_permlane32_swap(wd, wd, false, false);
             if (hf == 0) rowword[t][lr][kb] = both[0] | both[1];
         }
-        // tile t + 1 has landed: everything but the four loads of tile t + 2 just issued
-        __builtin_amdgcn_s_waitcnt(0x0F74);
+        // tile t + 1 has landed
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         lds_barrier();
     };
-    // fully unrolled (at most kMaskChunkTiles tiles, forward branches only): with loads left in
-    // flight across a loop's back edge the compiler falls back to waiting for all of them at the
-    // loop header
-    static_assert(kMaskChunkTiles == 16, "tile loop below is written out for 16 tiles");
-#pragma unroll
-    for (int t3 = 0; t3 < 18; t3 += 3) {
-        if (t3 >= ntiles) break;
-        tile_step(t3, kt0, kt2);
-        if (t3 + 1 >= ntiles) break;
-        tile_step(t3 + 1, kt1, kt0);
-        if (t3 + 2 >= ntiles) break;
-        tile_step(t3 + 2, kt2, kt1);
+    static_assert(kMaskChunkTiles % 2 == 0, "the tile loop below alternates two stages");
+#pragma unroll 1
+    for (int t2 = 0; t2 < ntiles; t2 += 2) {
+        tile_step(t2, kt0, kt1);
+        if (t2 + 1 >= ntiles) break;
+        tile_step(t2 + 1, kt1, kt0);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);              // the trailing loads have landed before LDS is reused
     combine_all();
