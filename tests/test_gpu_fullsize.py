@@ -85,3 +85,43 @@ def test_varlen_mixed_packed(api):
     assert worst["selected"] > 0.99 * worst["candidates"]   # no planted structure: nearly dense
     del run
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("step", [3, 16])
+def test_long_packed_every_key_chunk_of_every_row_tile(api, step):
+    """Sequences long enough for several tiles of pooled rows in the bf16 mask kernel (its grid pairs
+    a short row tile with a long one, per sequence: 4, 3 and 1 tiles here; 126 or 128 rows per tile).
+    theta = +inf must select every candidate of every group and theta = -inf none (a key chunk that no
+    work-group visits, or visits for the wrong tile, shows as a wrong count); at a finite theta
+    sampled groups from both ends of every row tile are compared with the oracle."""
+    from parity_util import GpuRun, check_groups
+    lens = (50000, 33000, 3000)
+    wl = synth.Workload("long_packed", "bf16", lens, 2, 1, 128, 128, 128, 128, step, 4.5, 123, n_planted=96,
+                        planted_mag=(2.5, 2.5), sink_keys=4, sink_mag=4.0)
+    seqs = [synth.make_sequence(wl, s, signal="logit") for s in range(wl.B)]
+    span = 128 * step
+    for theta in (float("inf"), float("-inf")):
+        run = GpuRun(api, seqs, _cfg(api, wl, theta=theta), "bf16", packed=True, want_acc=False)
+        B = run.buf
+        api.anchor_compute(run.p, run.q, run.k, run.v, B["M"], B["L"], None, B["xa"])
+        api.stripe_select(run.p, run.q, run.k, B["xa"], B["counts"], B["offsets"], B["idx"], B["flag"], B["ws"])
+        torch.cuda.synchronize()
+        assert int(B["flag"]) == 0
+        counts = B["counts"].cpu().numpy()
+        for b, n in enumerate(lens):
+            for h in range(wl.Hq):
+                for g in range((n + span - 1) // span):
+                    cand = max(0, max(wl.n_init, g * span - wl.window) - wl.n_init)
+                    assert counts[run.grp_index(b, h, g)] == (cand if theta > 0 else 0), (theta, b, h, g)
+        del run, B
+        torch.cuda.empty_cache()
+    rows_per_tile = (128 - 128 % step) // step          # groups per row tile
+    samples = []
+    for b, n in enumerate(lens):
+        ng = (n + span - 1) // span
+        edge = sorted({g for t in range(0, ng, rows_per_tile) for g in (t, min(ng - 1, t + rows_per_tile - 1))})
+        samples += [(b, (b + i) % wl.Hq, g) for i, g in enumerate(edge)]
+    run = GpuRun(api, seqs, _cfg(api, wl), "bf16", packed=True).stages()
+    assert int(run.buf["flag"]) == 0
+    worst = check_groups(run, samples)
+    assert 0 < worst["selected"] < worst["candidates"]
