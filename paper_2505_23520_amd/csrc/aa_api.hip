@@ -184,7 +184,7 @@ int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
             ea.sel_groups = pl.sz.groups;
             ea.sel_entries = 48ll * 64 * pl.sz.groups;   // mean list of 48 tiles
             ea.sel = 1;
-            hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(256), 0, st, ea);
+            if (!launch_engine_bf16(ea, grid, st)) return AA_EUNSUPPORTED;
             AA_LAUNCHED("engine_bf16_kernel");
             ea.sel = 2;
             hipLaunchKernelGGL(engine_bf16_pp_kernel, dim3(gridp), dim3(512), 0, st, ea);
@@ -193,7 +193,7 @@ int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
             hipLaunchKernelGGL(engine_bf16_pp_kernel, dim3(gridp), dim3(512), 0, st, ea);
             AA_LAUNCHED("engine_bf16_pp_kernel");
         } else {
-            hipLaunchKernelGGL(engine_bf16_kernel, dim3(grid), dim3(256), 0, st, ea);
+            if (!launch_engine_bf16(ea, grid, st)) return AA_EUNSUPPORTED;
             AA_LAUNCHED("engine_bf16_kernel");
         }
     } else {

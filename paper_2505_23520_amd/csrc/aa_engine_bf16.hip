@@ -73,7 +73,12 @@ __device__ __forceinline__ void both_halves(float x, float& u, float& v) {
 
 }  // namespace
 
+// FLAGS (a combination of kEng*) is a compile-time parameter: every mode gets its own code without
+// the other modes' branches, registers and, above all, merged control-flow paths (where paths with
+// different numbers of outstanding loads meet, the compiler's waits assume the shortest).
+template <int FLAGS>
 __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
+    constexpr int flags = FLAGS;
     constexpr int NW = 4;                            // waves per work-group
     static_assert(NW == 4, "the loader deals four groups of a tile to every wave");
     // one LDS object per stage, so that the compiler can tell that the asynchronous loads into
@@ -104,8 +109,8 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
 
     // ---- tile sequence: [range 1: initial tokens][range 2: window .. diagonal][list chunks]
     int W = 0, ninit = 0, T1 = 0, t2s = 0, nA = 0;
-    if (a.flags & kEngAnchorRegion) {
-        if (!(a.flags & kEngDense)) { W = window_start(p, g); ninit = p.n_init; }
+    if (flags & kEngAnchorRegion) {
+        if (!(flags & kEngDense)) { W = window_start(p, g); ninit = p.n_init; }
         const int e1 = min(ninit, rlast + 1);
         T1 = (e1 + TK - 1) / TK;
         t2s = max(T1, W / TK);
@@ -114,7 +119,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     }
     int cnt = 0;
     long long lbase = 0;
-    if (a.flags & kEngList) {
+    if (flags & kEngList) {
         const long long t = grp_index(p, sq, wk.b, wk.h, g);
         cnt = a.counts[t];
         lbase = a.offsets[t];
@@ -174,6 +179,11 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         }
     };
 
+    // The first list indices are requested before everything else: the first tile's loads need them,
+    // and only them, so they go out while the Q fragments and the cached state are still on their way
+    // (waits are in issue order: behind those loads the indices would arrive last).
+    if (nT > 0) idx_prefetch(0);
+
     // ---- Q fragments (B operand of S^T = K Q^T): lane (n, hf) holds Q[row][16 ks + 8 hf .. +8)
     bf16x8 qf[8];
     {
@@ -194,7 +204,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     const long long ri = row_index(p, sq, wk.b, wk.h, rok ? r : row0);
     float mref, mtrue, l;
     floatx16 o[4];
-    if (a.flags & kEngLoadState) {
+    if (flags & kEngLoadState) {
         mref = a.Min[ri] / p.sigma;
         mtrue = mref;
         l = hf == 0 ? a.Lin[ri] : 0.f;
@@ -217,7 +227,6 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
 
     // ---- pipeline prologue
     if (nT > 0) {
-        idx_prefetch(0);
         tile_load(0, Ks0, Vs0);
         idx_prefetch(1);
     }
@@ -361,7 +370,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         both_halves(l, u, w);
         lt = u + w;
     }
-    if (a.flags & kEngStoreState) {
+    if (flags & kEngStoreState) {
         // exported state is relative to the true maximum (Algorithm 1's m, l, acc)
         const float down = (mref == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mtrue) * c2);
         const float ms = mtrue * p.sigma;
@@ -389,7 +398,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             }
         }
     }
-    if ((a.flags & kEngStoreOut) && rok) {
+    if ((flags & kEngStoreOut) && rok) {
         const float inv = 1.f / lt;
         unsigned short* dst = (unsigned short*)a.out + tok_offset(p, p.os, sq, wk.b, wk.h, r);
 #pragma unroll
@@ -404,5 +413,18 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     }
 }
 
+
+bool launch_engine_bf16(const EngineArgs& ea, unsigned grid, hipStream_t st) {
+    switch (ea.flags) {
+#define AA_ENGINE_CASE(F) \
+    case (F): hipLaunchKernelGGL(engine_bf16_kernel<(F)>, dim3(grid), dim3(256), 0, st, ea); return true;
+    AA_ENGINE_CASE(kEngAnchorRegion | kEngStoreState)                 // stage 1
+    AA_ENGINE_CASE(kEngList | kEngLoadState | kEngStoreOut)           // stage 3 from the cached state
+    AA_ENGINE_CASE(kEngList | kEngAnchorRegion | kEngStoreOut)        // stage 3 recomputing the anchor region
+    AA_ENGINE_CASE(kEngAnchorRegion | kEngDense | kEngStoreOut)       // dense causal attention
+#undef AA_ENGINE_CASE
+    default: return false;
+    }
+}
 
 }  // namespace aa
