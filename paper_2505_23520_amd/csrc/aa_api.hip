@@ -187,10 +187,10 @@ int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
             if (!launch_engine_bf16(ea, grid, st)) return AA_EUNSUPPORTED;
             AA_LAUNCHED("engine_bf16_kernel");
             ea.sel = 2;
-            hipLaunchKernelGGL(engine_bf16_pp_kernel, dim3(gridp), dim3(512), 0, st, ea);
+            if (!launch_engine_bf16_pp(ea, gridp, st)) return AA_EUNSUPPORTED;
             AA_LAUNCHED("engine_bf16_pp_kernel");
         } else if (choice == 2) {
-            hipLaunchKernelGGL(engine_bf16_pp_kernel, dim3(gridp), dim3(512), 0, st, ea);
+            if (!launch_engine_bf16_pp(ea, gridp, st)) return AA_EUNSUPPORTED;
             AA_LAUNCHED("engine_bf16_pp_kernel");
         } else {
             if (!launch_engine_bf16(ea, grid, st)) return AA_EUNSUPPORTED;

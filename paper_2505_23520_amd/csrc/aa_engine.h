@@ -41,7 +41,7 @@ __device__ __forceinline__ bool engine_selected(const EngineArgs& a) {
 // 128 query rows per work-group, one instantiation per mode; false: no instantiation for ea.flags
 bool launch_engine_bf16(const EngineArgs& ea, unsigned grid, hipStream_t st);
 // 256 query rows (two consecutive blocks) per work-group; needs dense mode or an even step
-__global__ void engine_bf16_pp_kernel(EngineArgs a);
+bool launch_engine_bf16_pp(const EngineArgs& ea, unsigned grid, hipStream_t st);
 
 __global__ void engine_fp32_kernel(EngineArgs a);
 size_t engine_fp32_lds_bytes(int d, int bq);
