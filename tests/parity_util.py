@@ -20,7 +20,7 @@ def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
     return t.cuda()
 
 
-class GpuRun:
+class DeviceRun:
     """Runs the stage-wise entry points and the fused one on a batch of sequences."""
 
     def __init__(self, api, seqs, cfg, dtype, packed=None, want_acc=True):
@@ -122,7 +122,7 @@ def tolerances(dtype):
     return dict(M=2e-4, L=4e-3, accn=2e-2, xa=2e-4, O=2e-2, lse=4e-3)
 
 
-def check_groups(run: GpuRun, samples, check_state=True, out=None, lse=None):
+def check_groups(run: DeviceRun, samples, check_state=True, out=None, lse=None):
     """Compare GPU results with the oracle for (b, h, g) samples.  Returns summary stats."""
     cfg, d, tol = run.cfg, run.d, tolerances(run.dtype)
     op = oracle_params(cfg, d)

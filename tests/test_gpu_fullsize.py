@@ -24,9 +24,9 @@ def _cfg(api, wl, **kw):
 
 
 def _run(api, wl, cfg, signal, samples, packed=None):
-    from parity_util import GpuRun, check_groups
+    from parity_util import DeviceRun, check_groups
     seqs = [synth.make_sequence(wl, s, signal=signal) for s in range(wl.B)]
-    run = GpuRun(api, seqs, cfg, wl.dtype, packed=packed).stages()
+    run = DeviceRun(api, seqs, cfg, wl.dtype, packed=packed).stages()
     assert int(run.buf["flag"]) == 0
     worst = check_groups(run, samples)
     out, lse, stats = run.fused()
@@ -94,14 +94,14 @@ def test_long_packed_every_key_chunk_of_every_row_tile(api, step):
     theta = +inf must select every candidate of every group and theta = -inf none (a key chunk that no
     work-group visits, or visits for the wrong tile, shows as a wrong count); at a finite theta
     sampled groups from both ends of every row tile are compared with the oracle."""
-    from parity_util import GpuRun, check_groups
+    from parity_util import DeviceRun, check_groups
     lens = (50000, 33000, 3000)
     wl = synth.Workload("long_packed", "bf16", lens, 2, 1, 128, 128, 128, 128, step, 4.5, 123, n_planted=96,
                         planted_mag=(2.5, 2.5), sink_keys=4, sink_mag=4.0)
     seqs = [synth.make_sequence(wl, s, signal="logit") for s in range(wl.B)]
     span = 128 * step
     for theta in (float("inf"), float("-inf")):
-        run = GpuRun(api, seqs, _cfg(api, wl, theta=theta), "bf16", packed=True, want_acc=False)
+        run = DeviceRun(api, seqs, _cfg(api, wl, theta=theta), "bf16", packed=True, want_acc=False)
         B = run.buf
         api.anchor_compute(run.p, run.q, run.k, run.v, B["M"], B["L"], None, B["xa"])
         api.stripe_select(run.p, run.q, run.k, B["xa"], B["counts"], B["offsets"], B["idx"], B["flag"], B["ws"])
@@ -121,7 +121,7 @@ def test_long_packed_every_key_chunk_of_every_row_tile(api, step):
         ng = (n + span - 1) // span
         edge = sorted({g for t in range(0, ng, rows_per_tile) for g in (t, min(ng - 1, t + rows_per_tile - 1))})
         samples += [(b, (b + i) % wl.Hq, g) for i, g in enumerate(edge)]
-    run = GpuRun(api, seqs, _cfg(api, wl), "bf16", packed=True).stages()
+    run = DeviceRun(api, seqs, _cfg(api, wl), "bf16", packed=True).stages()
     assert int(run.buf["flag"]) == 0
     worst = check_groups(run, samples)
     assert 0 < worst["selected"] < worst["candidates"]

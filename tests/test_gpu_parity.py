@@ -41,11 +41,11 @@ def _all_samples(run):
 
 
 def _run_and_check(api, wl, cfg, signal="logit", samples=None, packed=None, edit=None):
-    from parity_util import GpuRun, check_groups
+    from parity_util import DeviceRun, check_groups
     seqs = [synth.make_sequence(wl, s, signal=signal) for s in range(wl.B)]
     if edit is not None:
         edit(seqs)
-    run = GpuRun(api, seqs, cfg, wl.dtype, packed=packed).stages()
+    run = DeviceRun(api, seqs, cfg, wl.dtype, packed=packed).stages()
     assert int(run.buf["flag"]) == 0
     smp = _all_samples(run) if samples is None else samples
     worst = check_groups(run, smp)
@@ -124,7 +124,7 @@ def test_bf16_short_sequences(api):
 
 @pytest.mark.parametrize("theta", [float("inf"), float("-inf")])
 def test_bf16_theta_extremes(api, theta):
-    from parity_util import GpuRun
+    from parity_util import DeviceRun
     wl = _wl("t", "bf16", [1536], 4, 2, 128, 128, 50, 16)
     cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=theta)
     run, worst = _run_and_check(api, wl, cfg)
@@ -139,12 +139,12 @@ def test_bf16_theta_extremes(api, theta):
 
 def test_dense_flash_matches_oracle(api):
     from oracle import anchor_oracle as ao
-    from parity_util import GpuRun
+    from parity_util import DeviceRun
     for dtype, d, block, N, tolO in (("bf16", 128, 128, 1100, 2e-2), ("fp32", 64, 64, 700, 1e-5)):
         wl = _wl("t", dtype, [N], 2, 1, d, block, 60, 8)
         seqs = [synth.make_sequence(wl, 0, signal="logit")]
         cfg = api.Config(block=block, n_init=block, window=block, step=1, theta=1.0)
-        run = GpuRun(api, seqs, cfg, dtype)
+        run = DeviceRun(api, seqs, cfg, dtype)
         out, lse = run.dense()
         for h in range(2):
             ref = ao.run_head(seqs[0]["q"][h], seqs[0]["k"][0], seqs[0]["v"][0], ao.dense_params(block))
@@ -154,11 +154,11 @@ def test_dense_flash_matches_oracle(api):
 
 def test_bf16_recompute_anchor_in_stage3(api):
     """sparse_attn with M = L = Acc = NULL computes the anchor region itself."""
-    from parity_util import GpuRun
+    from parity_util import DeviceRun
     wl = _wl("t", "bf16", [2048], 4, 2, 128, 128, 70, 32)
     cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=4.5)
     seqs = [synth.make_sequence(wl, 0, signal="logit")]
-    run = GpuRun(api, seqs, cfg, "bf16").stages()
+    run = DeviceRun(api, seqs, cfg, "bf16").stages()
     out2 = torch.zeros_like(run.out)
     lse2 = torch.empty_like(run.buf["lse"])
     B = run.buf
@@ -231,11 +231,11 @@ def test_packed_varlen(api):
 
 def test_fixed_batch_and_strided_layout(api):
     """B = 2 fixed-length batch; tensors given as [B, N, H, d] views (token-major memory)."""
-    from parity_util import GpuRun, check_groups
+    from parity_util import DeviceRun, check_groups
     wl = _wl("t", "bf16", [1024, 1024], 4, 2, 128, 128, 90, 16)
     cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=4.5)
     seqs = [synth.make_sequence(wl, s, signal="logit") for s in range(2)]
-    run = GpuRun(api, seqs, cfg, "bf16", packed=False)
+    run = DeviceRun(api, seqs, cfg, "bf16", packed=False)
     for name in ("q", "k", "v", "out"):
         t = getattr(run, name)
         setattr(run, name, t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3))   # same values, other strides
@@ -246,11 +246,11 @@ def test_fixed_batch_and_strided_layout(api):
 
 
 def test_overflow_flag_and_capacity(api):
-    from parity_util import GpuRun
+    from parity_util import DeviceRun
     wl = _wl("t", "bf16", [2048], 2, 1, 128, 128, 95, 64)
     cfg = api.Config(block=128, n_init=128, window=128, step=1, theta=float("inf"))
     seqs = [synth.make_sequence(wl, 0, signal="logit")]
-    run = GpuRun(api, seqs, cfg, "bf16")
+    run = DeviceRun(api, seqs, cfg, "bf16")
     B = run.buf
     api.anchor_compute(run.p, run.q, run.k, run.v, B["M"], B["L"], B["Acc"], B["xa"])
     small = torch.full((1024 + 64,), -7, dtype=torch.int32, device="cuda")
@@ -263,11 +263,11 @@ def test_overflow_flag_and_capacity(api):
 
 
 def test_determinism(api):
-    from parity_util import GpuRun
+    from parity_util import DeviceRun
     wl = _wl("t", "bf16", [3000], 4, 2, 128, 128, 97, 40)
     cfg = api.Config(block=128, n_init=128, window=128, step=4, theta=5.0)
     seqs = [synth.make_sequence(wl, 0, signal="logit")]
-    run = GpuRun(api, seqs, cfg, "bf16").stages()
+    run = DeviceRun(api, seqs, cfg, "bf16").stages()
     o1, i1, c1 = run.out.clone(), run.buf["idx"].clone(), run.buf["counts"].clone()
     run.stages()
     tot = int(run.buf["offsets"][-1])
