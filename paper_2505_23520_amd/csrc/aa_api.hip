@@ -41,7 +41,7 @@ struct Plan {
     aa_sizes sz;
     int nwords;
     // byte offsets inside the workspaces
-    size_t sel_qhi, sel_qlo, sel_bits, sel_kp;               // stripe_select workspace
+    size_t sel_qhi, sel_qlo, sel_bits, sel_segc, sel_kp;               // stripe_select workspace
     size_t pf_M, pf_L, pf_Acc, pf_xa, pf_counts, pf_offsets, pf_flag, pf_idx, pf_sel;  // prefill workspace
 };
 
@@ -142,6 +142,7 @@ int make_plan(const aa_params* p, Plan* pl) {
         pl->sel_qlo = off;
     }
     pl->sel_bits = off; off += align256((size_t)s.groups * pl->nwords * 4);
+    pl->sel_segc = off; off += align256((size_t)s.groups * cdiv(pl->nwords, 64) * 4);
     pl->sel_kp = off;
     if (p->granularity == AA_BLOCK) off += align256((size_t)(s.blocks / k.grp) * p->d * 4);
     s.select_ws_bytes = off;
@@ -231,6 +232,8 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     sa.qp_hi = ws + pl.sel_qhi; sa.qp_lo = ws + pl.sel_qlo; sa.qp_f32 = (float*)(ws + pl.sel_qhi);
     sa.bits = (unsigned*)(ws + pl.sel_bits);
     sa.kp_f32 = (float*)(ws + pl.sel_kp);
+    sa.segcount = (int*)(ws + pl.sel_segc);
+    sa.nseg = (int)cdiv(pl.nwords, 64);
     sa.is_bf16 = p->dtype == AA_BF16;
     sa.nwords = pl.nwords;
     sa.keys_per_chunk = kMaskChunkKeys * kMaskChunksPerWG;
@@ -278,11 +281,11 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
         hipLaunchKernelGGL(mask_fp32_kernel, gm, dim3(256), (size_t)kp.step * kp.d * 4, st, sa);
         AA_LAUNCHED("mask_fp32_kernel");
     }
-    hipLaunchKernelGGL(count_kernel, ggrp, dim3(64), 0, st, sa);
+    hipLaunchKernelGGL(count_kernel, ggrp, dim3(256), 0, st, sa);
     AA_LAUNCHED("count_kernel");
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, sa);
     AA_LAUNCHED("scan_kernel");
-    hipLaunchKernelGGL(fill_kernel, ggrp, dim3(256), 0, st, sa);
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)cdiv(sa.nseg, 4), kp.ngrp_max, kp.Hq * kp.B), dim3(256), 0, st, sa);
     AA_LAUNCHED("fill_kernel");
     return AA_OK;
 }

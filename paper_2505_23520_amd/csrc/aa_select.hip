@@ -463,8 +463,9 @@ __global__ void zero_i32_kernel(int* x, long long nelem) {
     if (i < nelem) x[i] = 0;
 }
 
-// grid (ngrp_max, Hq, B), 64 threads
-__global__ __launch_bounds__(64) void count_kernel(SelectArgs a) {
+// grid (ngrp_max, Hq, B), 256 threads: selected columns of the group, in total and per segment of
+// 64 bit words (the segment counts let fill_kernel expand the segments independently)
+__global__ __launch_bounds__(256) void count_kernel(SelectArgs a) {
     const KParams& p = a.p;
     const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const Seq sq = seq_of(p, b);
@@ -473,12 +474,22 @@ __global__ __launch_bounds__(64) void count_kernel(SelectArgs a) {
     const int Wg = window_start(p, g);
     const long long t = grp_index(p, sq, b, h, g);
     const unsigned* bits = a.bits + t * a.nwords;
-    int c = 0;
-    if (Wg > p.n_init)
-        for (int w = p.n_init / 32 + threadIdx.x; w < (Wg + 31) / 32; w += 64) c += __popc(bits[w]);
+    int* segc = a.segcount + t * a.nseg;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int w_lo = p.n_init / 32, w_hi = Wg > p.n_init ? (Wg + 31) / 32 : w_lo;
+    int total = 0;
+    for (int seg = wave; seg * 64 < w_hi; seg += 4) {
+        const int w = seg * 64 + lane;
+        int c = (w >= w_lo && w < w_hi) ? __popc(bits[w]) : 0;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);
-    if (threadIdx.x == 0) a.counts[t] = c;
+        for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);
+        if (lane == 0) segc[seg] = c;
+        total += c;
+    }
+    __shared__ int wsum[4];
+    if (lane == 0) wsum[wave] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) a.counts[t] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
 }
 
 // one work-group of 1024 threads: offsets[t] = sum_{t' < t} roundup64(counts[t'])
@@ -509,57 +520,60 @@ __global__ __launch_bounds__(1024) void scan_kernel(SelectArgs a) {
     }
 }
 
-// grid (ngrp_max, Hq, B), 256 threads: expand the group's bit words into its ascending list
+// grid (ceil(nseg / 4), ngrp_max, B*Hq), 256 threads: each wave expands one segment (64 bit words =
+// 2048 keys) of the group's bit words into its part of the ascending list; the segment counts give
+// its position.  No barriers: a wave without work returns.
 __global__ __launch_bounds__(256) void fill_kernel(SelectArgs a) {
     const KParams& p = a.p;
-    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int g = blockIdx.y, h = blockIdx.z % p.Hq, b = blockIdx.z / p.Hq;
     const Seq sq = seq_of(p, b);
     const int ngrp = (sq.len + p.bq * p.step - 1) / (p.bq * p.step);
     if (g >= ngrp) return;
     const int Wg = window_start(p, g);
     if (Wg <= p.n_init) return;
-    const long long t = grp_index(p, sq, b, h, g);
-    const int cnt = a.counts[t];
-    if (cnt == 0) return;
-    const long long base = a.offsets[t];
-    const unsigned* bits = a.bits + t * a.nwords;
+    const int lane = threadIdx.x & 63;
+    const int seg = __builtin_amdgcn_readfirstlane(4 * blockIdx.x + (threadIdx.x >> 6));
     const int w_lo = p.n_init / 32, w_hi = (Wg + 31) / 32;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // each wave takes a contiguous quarter of the words
-    const int per = (w_hi - w_lo + 3) / 4;
-    const int a0 = min(w_hi, w_lo + wave * per), a1 = min(w_hi, a0 + per);
-    int c = 0;
-    for (int w = a0 + lane; w < a1; w += 64) c += __popc(bits[w]);
+    if (seg * 64 >= w_hi) return;
+    const long long t = grp_index(p, sq, b, h, g);
+    // every load is issued before the first decision, so the wave pays one memory round trip
+    const int* segc = a.segcount + t * a.nseg;
+    const int cnt = a.counts[t];
+    const int own = segc[seg];
+    const long long base = a.offsets[t];
+    int pre = 0;                                         // selected columns in earlier segments
+    for (int s = lane; s < seg; s += 64) pre += segc[s];
+    const int w = seg * 64 + lane;                       // this lane's word
+    const unsigned wd = (w >= w_lo && w < w_hi) ? a.bits[t * a.nwords + w] : 0u;
+    if (own == 0) return;                                // the group's last entry is never in such a segment
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);
-    __shared__ int wsum[4];
-    __shared__ int last_key;
-    if (lane == 0) wsum[wave] = c;
-    __syncthreads();
-    long long pos = base;
-    for (int i = 0; i < wave; ++i) pos += wsum[i];
-    // two words per step: lanes 0..31 test word w, lanes 32..63 word w+1
-    for (int w = a0; w < a1; w += 2) {
-        const int wi = w + (lane >> 5);
-        const unsigned wd = wi < a1 ? bits[wi] : 0u;
-        const unsigned first = __shfl(wd, 0, 64);      // word w as seen by every lane
-        const int bit = lane & 31;
-        const bool on = (wd >> bit) & 1u;
-        const int before = __popc(wd & ((1u << bit) - 1u)) + ((lane >> 5) ? __popc(first) : 0);
-        const long long dst = pos + before;
-        if (on && dst < a.idx_capacity) a.idx[dst] = wi * 32 + bit;
-        pos += __popc(first) + __popc(__shfl(wd, 32, 64));
+    for (int off = 32; off >= 1; off >>= 1) pre += __shfl_xor(pre, off, 64);
+    // two words per step: lanes 0..31 test word 2 i, lanes 32..63 word 2 i + 1 (coalesced stores)
+    long long pos = base + pre;
+    const int bit = lane & 31, half = lane >> 5;
+    // only the word pairs that hold a selected column are visited (scalar loop over a bit mask)
+    const unsigned long long nzw = __ballot(wd != 0u);
+    unsigned long long pairs = (nzw | (nzw >> 1)) & 0x5555555555555555ull;
+    while (pairs) {
+        const int i = __builtin_ctzll(pairs) >> 1;
+        pairs &= pairs - 1;
+        const unsigned first = __builtin_amdgcn_readlane(wd, 2 * i), second = __builtin_amdgcn_readlane(wd, 2 * i + 1);
+        const unsigned mine = half ? second : first;
+        const bool on = (mine >> bit) & 1u;
+        const long long dst = pos + __popc(mine & ((1u << bit) - 1u)) + (half ? __popc(first) : 0);
+        if (on && dst < a.idx_capacity) a.idx[dst] = (seg * 64 + 2 * i + half) * 32 + bit;
+        pos += __popc(first) + __popc(second);
     }
-    // padding up to the next multiple of 64 repeats the last entry
-    if (tid == 0) {
-        int w = w_hi - 1;
-        while (w > w_lo && bits[w] == 0u) --w;
-        last_key = w * 32 + 31 - __clz(bits[w]);
+    // the wave that wrote the group's last entry pads the list to the next multiple of 64 with it
+    if (pre + own == cnt) {
+        const unsigned long long nz = __ballot(wd != 0u);
+        const int top = 63 - __builtin_clzll(nz);        // own > 0: some word is non-zero
+        const unsigned lastw = __shfl(wd, top, 64);
+        const int last_key = (seg * 64 + top) * 32 + 31 - __clz(lastw);
+        const int padded = (cnt + kIdxPad - 1) / kIdxPad * kIdxPad;
+        for (int e = cnt + lane; e < padded; e += 64)
+            if (base + e < a.idx_capacity) a.idx[base + e] = last_key;
     }
-    __syncthreads();
-    const int padded = (cnt + kIdxPad - 1) / kIdxPad * kIdxPad;
-    for (int e = cnt + tid; e < padded; e += 256)
-        if (base + e < a.idx_capacity) a.idx[base + e] = last_key;
 }
 
 }  // namespace aa
