@@ -272,3 +272,33 @@ def test_determinism(api):
     run.stages()
     tot = int(run.buf["offsets"][-1])
     assert torch.equal(o1, run.out) and torch.equal(c1, run.buf["counts"]) and torch.equal(i1[:tot], run.buf["idx"][:tot])
+
+
+# ------------------------------------------------------------------ seeded random configurations
+def _random_cases():
+    rng = np.random.default_rng(20250523)
+    cases = []
+    for i in range(14):
+        bf16 = i % 7 != 6                       # twelve bf16 cases, two fp32 cases
+        block = 128 if bf16 else int(rng.choice([16, 32, 48, 64]))
+        d = 128 if bf16 else int(rng.choice([32, 64, 128]))
+        heads = [(2, 1), (4, 2), (4, 4), (8, 2), (3, 1)][int(rng.integers(5))]
+        nseq = int(rng.integers(1, 4))
+        hi = 5000 if bf16 else 700
+        lens = [int(rng.integers(1, hi)) for _ in range(nseq)]
+        step = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16]))
+        n_init = int(rng.integers(0, 3 * block))
+        window = int(rng.integers(0, 3 * block))
+        theta = float(rng.uniform(2.0, 5.5))
+        cases.append(("bf16" if bf16 else "fp32", d, block, heads, lens, step, n_init, window, theta, 300 + i))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(), ids=lambda c: "%s-N%s-s%d-i%d-w%d" % (c[0], "_".join(map(str, c[4])), c[5], c[6], c[7]))
+def test_random_configurations(api, case):
+    """Shapes nobody picked by hand: lengths, step, sink and window sizes, GQA ratio and batch
+    drawn from a fixed seed; packed when there is more than one sequence."""
+    dtype, d, block, (Hq, Hkv), lens, step, n_init, window, theta, seed = case
+    wl = _wl("rnd", dtype, lens, Hq, Hkv, d, block, seed, max(4, max(lens) // 48))
+    cfg = api.Config(block=block, n_init=n_init, window=window, step=step, theta=theta)
+    _run_and_check(api, wl, cfg, packed=(len(lens) > 1) or None)
