@@ -67,7 +67,7 @@ enum { AA_STRIPE = 0, AA_BLOCK = 1 };   /* identification granularity (b_q, 1) o
 enum {
     AA_OK = 0,
     AA_EINVAL = -1,       /* null pointer, non-positive size, Hq % Hkv != 0, bad stride ... */
-    AA_EUNSUPPORTED = -2, /* a combination the kernels do not implement (see anchor_check)  */
+    AA_EUNSUPPORTED = -2, /* a combination the kernels do not implement (aa_params fields)   */
     AA_EWORKSPACE = -3,   /* workspace smaller than anchor_sizes() reports                  */
     AA_EHIP = -4          /* a kernel launch failed; hipGetLastError text via anchor_last_hip_error */
 };

@@ -236,7 +236,6 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     sa.nseg = (int)cdiv(pl.nwords, 64);
     sa.is_bf16 = p->dtype == AA_BF16;
     sa.nwords = pl.nwords;
-    sa.keys_per_chunk = kMaskChunkKeys * kMaskChunksPerWG;
     sa.counts = counts; sa.offsets = (long long*)offsets; sa.idx = idx;
     sa.idx_capacity = cap; sa.overflow = flag;
     sa.groups_total = pl.sz.groups;

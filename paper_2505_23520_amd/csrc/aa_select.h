@@ -48,7 +48,6 @@ struct SelectArgs {
     int is_bf16;              // element type of q, k
     unsigned* bits;           // [groups][nwords] selection bit words, bit (j % 32) of word j / 32
     int nwords;               // ceil(N / 32)
-    int keys_per_chunk;       // bf16 mask kernel: keys per work-group, kMaskChunkKeys * kMaskChunksPerWG
     int* segcount;            // [groups][nseg] selected columns per segment of 64 bit words (2048 keys)
     int nseg;                 // ceil(nwords / 64)
     int* counts;
