@@ -364,6 +364,11 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     }
 
     // ---- epilogue
+    // The tile stages are free now (every wave has passed the barrier that ends the last tile):
+    // each wave takes one of them as a private staging area for coalesced stores.  LDS operations
+    // of one wave execute in order, so no barrier separates its writes from its reads.
+    char* const stg = wave == 0 ? Ks0 : wave == 1 ? Ks1 : wave == 2 ? Vs0 : Vs1;
+    const int wave_rows = min(32, sq.len - rw);      // rows of this wave inside the sequence (<= 0: none)
     float lt;                                        // row sum relative to mref
     {
         float u, w;
@@ -375,15 +380,29 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         const float down = (mref == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mtrue) * c2);
         const float ms = mtrue * p.sigma;
         if (rok && hf == 0) { a.Mout[ri] = ms; a.Lout[ri] = lt * down; }
-        if (rok && a.Accout) {
-            float* acc = a.Accout + ri * D;
+        if (a.Accout && wave_rows > 0) {
+            // 16 rows at a time: fragment layout -> row-major in LDS (pitch 132 floats), then 1 KB
+            // contiguous per store instruction (the wave's rows are contiguous in Acc)
+            float* sf = (float*)stg;
+            float* acc = a.Accout + row_index(p, sq, wk.b, wk.h, rw) * D;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int ph = 0; ph < 2; ++ph) {
+                if ((n >> 4) == ph) {
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4)
-                    *(floatx4*)(acc + 32 * db + 8 * v4 + 4 * hf) =
-                        floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
-                                o[db][4 * v4 + 3] * down};
+                    for (int db = 0; db < 4; ++db)
+#pragma unroll
+                        for (int v4 = 0; v4 < 4; ++v4)
+                            *(floatx4*)(sf + (n & 15) * 132 + 32 * db + 8 * v4 + 4 * hf) =
+                                floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
+                                        o[db][4 * v4 + 3] * down};
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int f4 = 64 * i + lane, row = f4 >> 5, c4 = f4 & 31;
+                    const floatx4 x = *(const floatx4*)(sf + row * 132 + 4 * c4);
+                    if (16 * ph + row < wave_rows) *(floatx4*)(acc + (16 * ph + row) * D + 4 * c4) = x;
+                }
+            }
         }
         if (a.xa) {
             // pooled anchor of the block: mean of M over its rows (Algorithm 2, avgpool of the anchor)
@@ -398,18 +417,27 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             }
         }
     }
-    if ((flags & kEngStoreOut) && rok) {
+    if ((flags & kEngStoreOut) && wave_rows > 0) {
+        // the wave's 32 output rows go through LDS (pitch 136 bf16) so that 16 lanes write one
+        // 256-byte row together instead of every lane writing 8-byte pieces of its own row
         const float inv = 1.f / lt;
-        unsigned short* dst = (unsigned short*)a.out + tok_offset(p, p.os, sq, wk.b, wk.h, r);
+        unsigned short* sb = (unsigned short*)stg;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
                 const floatx4 x = {o[db][4 * v4] * inv, o[db][4 * v4 + 1] * inv, o[db][4 * v4 + 2] * inv,
                                    o[db][4 * v4 + 3] * inv};
-                *(bf16x4*)(dst + 32 * db + 8 * v4 + 4 * hf) = __builtin_convertvector(x, bf16x4);
+                *(bf16x4*)(sb + n * 136 + 32 * db + 8 * v4 + 4 * hf) = __builtin_convertvector(x, bf16x4);
             }
-        if (a.lse && hf == 0) a.lse[ri] = mref * p.sigma + __logf(lt);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int f = 64 * i + lane, row = f >> 4, c = f & 15;
+            const intx4 x = *(const intx4*)(sb + row * 136 + 8 * c);
+            if (row < wave_rows)
+                *(intx4*)((unsigned short*)a.out + tok_offset(p, p.os, sq, wk.b, wk.h, rw + row) + 8 * c) = x;
+        }
+        if (rok && a.lse && hf == 0) a.lse[ri] = mref * p.sigma + __logf(lt);
     }
 }
 
