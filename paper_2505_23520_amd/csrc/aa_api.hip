@@ -284,7 +284,7 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     AA_LAUNCHED("count_kernel");
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, sa);
     AA_LAUNCHED("scan_kernel");
-    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)cdiv(sa.nseg, 4), kp.ngrp_max, kp.Hq * kp.B), dim3(256), 0, st, sa);
+    hipLaunchKernelGGL(fill_kernel, dim3(kp.ngrp_max, (unsigned)cdiv(sa.nseg, 4), kp.Hq * kp.B), dim3(256), 0, st, sa);
     AA_LAUNCHED("fill_kernel");
     return AA_OK;
 }

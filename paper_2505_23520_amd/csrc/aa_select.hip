@@ -520,19 +520,19 @@ __global__ __launch_bounds__(1024) void scan_kernel(SelectArgs a) {
     }
 }
 
-// grid (ceil(nseg / 4), ngrp_max, B*Hq), 256 threads: each wave expands one segment (64 bit words =
+// grid (ngrp_max, ceil(nseg / 4), B*Hq), 256 threads: each wave expands one segment (64 bit words =
 // 2048 keys) of the group's bit words into its part of the ascending list; the segment counts give
 // its position.  No barriers: a wave without work returns.
 __global__ __launch_bounds__(256) void fill_kernel(SelectArgs a) {
     const KParams& p = a.p;
-    const int g = blockIdx.y, h = blockIdx.z % p.Hq, b = blockIdx.z / p.Hq;
+    const int g = blockIdx.x, h = blockIdx.z % p.Hq, b = blockIdx.z / p.Hq;
     const Seq sq = seq_of(p, b);
     const int ngrp = (sq.len + p.bq * p.step - 1) / (p.bq * p.step);
     if (g >= ngrp) return;
     const int Wg = window_start(p, g);
     if (Wg <= p.n_init) return;
     const int lane = threadIdx.x & 63;
-    const int seg = __builtin_amdgcn_readfirstlane(4 * blockIdx.x + (threadIdx.x >> 6));
+    const int seg = __builtin_amdgcn_readfirstlane(4 * blockIdx.y + (threadIdx.x >> 6));
     const int w_lo = p.n_init / 32, w_hi = (Wg + 31) / 32;
     if (seg * 64 >= w_hi) return;
     const long long t = grp_index(p, sq, b, h, g);
