@@ -73,7 +73,8 @@ enum {
 };
 
 typedef struct aa_params {
-    int32_t B, Hq, Hkv;       /* batch (sequences), query heads, KV heads (Hq % Hkv == 0)      */
+    int32_t B, Hq, Hkv;       /* batch (sequences), query heads, KV heads (Hq % Hkv == 0;      */
+                              /* B * Hq <= 65535)                                              */
     int32_t N;                /* sequence length; longest sequence when cu_seqlens != NULL     */
     int32_t d;                /* head dimension: bf16 -> 128; fp32 -> 32, 64 or 128             */
     int32_t block_q;          /* b_q : bf16 -> 128; fp32 -> 16..128, multiple of 16             */

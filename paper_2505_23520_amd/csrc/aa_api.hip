@@ -105,6 +105,9 @@ int make_plan(const aa_params* p, Plan* pl) {
     const long long span = (long long)p->block_q * p->step;
     k.nblk_max = (int)cdiv(p->N, p->block_q);
     k.ngrp_max = (int)cdiv(p->N, span);
+    // launch grids put heads (times sequences) on y / z, and the fp32 mask kernel puts groups on y
+    if ((long long)p->Hq * p->B > 65535) return AA_EUNSUPPORTED;
+    if (p->dtype == AA_FP32 && k.ngrp_max > 65535) return AA_EUNSUPPORTED;
 
     aa_sizes& s = pl->sz;
     memset(&s, 0, sizeof(s));

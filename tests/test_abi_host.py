@@ -56,6 +56,7 @@ def test_sizes_arithmetic(api):
     (dict(theta=float("nan")), -1), (dict(dtype=7), -1), (dict(granularity=2), -1),
     (dict(granularity=1, n_init=64), -1), (dict(granularity=1, window=100), -1),
     (dict(causal=0), -2), (dict(d=64), -2), (dict(step=129), -2), (dict(block_q=64, block_kv=64), -2),
+    (dict(B=4096, Hq=32, Hkv=8), -2),      # heads x sequences beyond a launch grid's y / z range
 ])
 def test_rejects_bad_params(api, kw, code):
     with pytest.raises(api.AnchorError) as e:
