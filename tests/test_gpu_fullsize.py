@@ -125,3 +125,31 @@ def test_long_packed_every_key_chunk_of_every_row_tile(api, step):
     assert int(run.buf["flag"]) == 0
     worst = check_groups(run, samples)
     assert 0 < worst["selected"] < worst["candidates"]
+
+
+def test_256k_tokens_two_heads(api):
+    """Twice the headline length (more than 64 list segments and 16 mask row tiles per head): every
+    candidate at theta = +inf (and the output then equals dense attention), sampled groups against
+    the oracle at the workload's theta."""
+    from parity_util import DeviceRun, check_groups
+    N, step = 262144, 16
+    wl = synth.Workload("gqa_256k_2h", "bf16", (N,), 2, 1, 128, 128, 128, 128, step, float(np.log(32.0)), 77,
+                        n_planted=2048, planted_mag=(1.5, 3.5), sink_keys=4, sink_mag=4.0)
+    seqs = [synth.make_sequence(wl, 0, signal="logit")]
+    span = 128 * step
+    run = DeviceRun(api, seqs, _cfg(api, wl, theta=float("inf")), "bf16").stages()
+    assert int(run.buf["flag"]) == 0
+    counts = run.buf["counts"].cpu().numpy()
+    for h in range(2):
+        for g in range(N // span):
+            assert counts[run.grp_index(0, h, g)] == max(0, max(128, g * span - 128) - 128), (h, g)
+    dense, dlse = run.dense()
+    rows = torch.tensor([0, 1, 127, 128, 4095, 131071, 131072, 200000, N - 1], device="cuda")
+    for h in range(2):
+        assert (dense[0, h, rows].float() - run.out[0, h, rows].float()).abs().max().item() <= 2e-2
+    del run, dense, dlse
+    torch.cuda.empty_cache()
+    run = DeviceRun(api, seqs, _cfg(api, wl), "bf16").stages()
+    assert int(run.buf["flag"]) == 0
+    worst = check_groups(run, [(0, 0, 0), (0, 1, 1), (0, 0, 64), (0, 1, 127)])
+    assert 0 < worst["selected"] < 0.1 * worst["candidates"]
