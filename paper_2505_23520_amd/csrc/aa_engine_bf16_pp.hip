@@ -412,7 +412,10 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
         slot_barrier();
         // everything but the index fetch just issued, which is the youngest load
         if (has_list) __builtin_amdgcn_s_waitcnt(0x0F71); else wait_vmem();
+        // the wave in its MFMA phase wins issue arbitration against its SIMD sibling's vector ALU work (+1 %)
+        __builtin_amdgcn_s_setprio(2);
         mfma_phase(Knext, Vcur, Kld, Vld, min(t + la, nT - 1), keys);
+        __builtin_amdgcn_s_setprio(0);
         slot_barrier();
     };
     // whole rounds of three tiles (one per LDS stage); tiles past the end only keep the barriers
