@@ -96,10 +96,10 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     const Seq sq = seq_of(p, wk.b);
     const int row0 = wk.i * BQ;
     if (row0 >= sq.len) return;
-    // The two waves that share a SIMD (one from each resident work-group) sit in wave slots 0 and 1
-    // (HW_ID bits 3:0).  The odd slot gets the higher issue priority, so the pair does not settle
-    // into lockstep (both in their MFMA phase, then both in their softmax phase) but interleaves.
-    if (__builtin_amdgcn_s_getreg(0x1804) & 1) __builtin_amdgcn_s_setprio(2);
+    // Two waves share a SIMD (one from each resident work-group).  A wave raises its issue priority
+    // for its MFMA blocks and drops it for its softmax, so a wave with matrix work wins over a
+    // sibling that is in its vector-ALU part, and the pair does not settle into lockstep.
+    __builtin_amdgcn_s_setprio(2);
     const int hk = wk.h / p.grp;
     const int g = wk.i / p.step;
     const int rw = row0 + 32 * wave;                 // first row of this wave
@@ -302,6 +302,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
 
+        __builtin_amdgcn_s_setprio(0);
         // online softmax of this lane's query row (the other half of the row is 32 lanes away)
         float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
@@ -339,6 +340,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
             }
         l += rs;
 
+        __builtin_amdgcn_s_setprio(2);
         // O^T += V^T P^T
 #pragma unroll
         for (int sg = 0; sg < 4; ++sg)
