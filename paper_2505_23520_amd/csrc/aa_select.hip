@@ -230,6 +230,9 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
     lds_barrier();
     auto tile_step = [&](int t, const char* Kcur, char* Kld) {
         load_tile(chunk0 + min(t + 1, ntiles - 1) * kMaskTileKeys, Kld);
+        // higher issue priority for the MFMA block than for the bit packing: a wave with matrix work
+        // wins over the SIMD's other waves that are in their vector-ALU part (-3 %)
+        __builtin_amdgcn_s_setprio(2);
         const char* Kb = Kcur + koff;
         floatx16 c[2];
         // the two accumulators alternate, so no MFMA waits for the one issued just before it
@@ -250,6 +253,7 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_s_setprio(0);
         // Threshold test xbar - sigma s <= theta as the sign of sigma s + (theta - xbar): two
         // instructions per score (fma, then the sign bit is shifted into a word), no compare / select
         // chains.  The lane gathers the bits of its 16 keys per 32-key block (accumulator register v
