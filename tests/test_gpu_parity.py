@@ -302,3 +302,51 @@ def test_random_configurations(api, case):
     wl = _wl("rnd", dtype, lens, Hq, Hkv, d, block, seed, max(4, max(lens) // 48))
     cfg = api.Config(block=block, n_init=n_init, window=window, step=step, theta=theta)
     _run_and_check(api, wl, cfg, packed=(len(lens) > 1) or None)
+
+
+def test_prefill_under_graph_capture(api, engine_mode):
+    """The fused entry point only enqueues kernels (no allocation, no synchronisation, no memset), so
+    it can be captured into a HIP graph: replays, with eager work of the same library between them,
+    reproduce the eager result bit for bit, also after the inputs change in place."""
+    from parity_util import DeviceRun
+    wl = _wl("t", "bf16", [3000], 4, 2, 128, 128, 61, 48)
+    cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=4.0)
+    seqs = [synth.make_sequence(wl, 0, signal="logit")]
+    run = DeviceRun(api, seqs, cfg, "bf16")
+    sz = run.sizes
+    ws = torch.empty(sz.prefill_ws_bytes, dtype=torch.uint8, device="cuda")
+    lse = torch.empty(sz.rows, dtype=torch.float32, device="cuda")
+    stats = torch.zeros(4, dtype=torch.int64, device="cuda")
+    out = torch.zeros_like(run.q)
+
+    def eager():
+        o = torch.zeros_like(run.q)
+        l = torch.empty_like(lse)
+        st = torch.zeros_like(stats)
+        w = torch.empty_like(ws)
+        api.anchor_attention_prefill(run.p, run.q, run.k, run.v, o, l, st, w)
+        torch.cuda.synchronize()
+        return o, l, st
+
+    ref_o, ref_l, ref_st = eager()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up on the capture stream
+        api.anchor_attention_prefill(run.p, run.q, run.k, run.v, out, lse, stats, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        api.anchor_attention_prefill(run.p, run.q, run.k, run.v, out, lse, stats, ws)
+    for rep in range(3):
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_o) and torch.equal(lse, ref_l) and torch.equal(stats, ref_st), rep
+        eager()                                         # the library's own eager work between replays
+    # new inputs in the same buffers: the replay follows them
+    run.q.copy_(run.q.flip(2).contiguous())
+    ref_o, ref_l, ref_st = eager()
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref_o) and torch.equal(lse, ref_l) and torch.equal(stats, ref_st)
