@@ -69,10 +69,8 @@ __device__ __forceinline__ void slot_barrier() {
 
 }  // namespace
 
-// FLAGS >= 0: compile-time mode, as in engine_bf16_kernel; FLAGS < 0: the mode is read from the
-// arguments.  Dense attention runs 4 % faster with the mode compiled in; the list-driven modes
-// measured 8 % slower that way (the simplified tile sequence schedules worse) and keep the
-// run-time mode.
+// FLAGS >= 0: compile-time mode, as in engine_bf16_kernel (the two modes that matter: stage 3
+// from the cached state and dense attention); FLAGS < 0: the mode is read from the arguments.
 template <int FLAGS>
 __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
     const int flags = FLAGS >= 0 ? FLAGS : a.flags;
@@ -263,45 +261,39 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
                                                          (int)(is_list ? ol : oc), 0, 0, 0);
             }
         }
+        // Issue order written out and pinned with scheduling fences (a sched_group_barrier
+        // pipeline for the same order is honoured in some instantiations of this kernel and not in
+        // others): K operands run four MFMAs ahead; the V operands (two transposing reads each) of
+        // the first four P V MFMAs are read under the last four score MFMAs, then four ahead.
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 kf[16];
+        shortx4 vlo[16], vhi[16];
+        auto read_k = [&](int i) { kf[i] = *(const bf16x8*)(Kb + 512 * (i & 1) + 32 * (i >> 1)); };
+        auto read_v = [&](int i) {                 // operand of P V MFMA i: sg = i / 4, db = i % 4
+            // keys 16 sg + 8 rd + 4 hf + (0..3) live in groups 8 rd + 4 hf + (0..3), row sg
+            vlo[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) shortx4*)(Vb + (i >> 2) * 256 + 64 * (i & 3)));
+            vhi[i] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) shortx4*)(Vb + 8 * VGRP + (i >> 2) * 256 + 64 * (i & 3)));
+        };
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+        for (int i = 0; i < 4; ++i) read_k(i);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb + 32 * ks);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? kZero16 : s[kb], 0, 0, 0);
-            }
-#pragma unroll
-        for (int sg = 0; sg < 4; ++sg)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                // keys 16 sg + 8 rd + 4 hf + (0..3) live in groups 8 rd + 4 hf + (0..3), row sg
-                const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4*)(Vb + sg * 256 + 64 * db));
-                const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) shortx4*)(Vb + 8 * VGRP + sg * 256 + 64 * db));
-                const shortx8 vv = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf[sg >> 1][sg & 1],
-                                                                 o[db], 0, 0, 0);
-            }
-        // program order of the reads: 16 K reads, then 32 V reads; the four tile loads come first
-        __builtin_amdgcn_sched_group_barrier(0x020, 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);              // K operands of QK 0..3
-#pragma unroll
-        for (int j = 0; j < 12; ++j) {                                  // QK 0..11: K read j + 4
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        for (int i = 0; i < 16; ++i) {             // score MFMA i: ks = i / 2, kb = i % 2
+            s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[i >> 1], i < 2 ? kZero16 : s[i & 1], 0, 0, 0);
+            if (i + 4 < 16) read_k(i + 4); else read_v(i - 12);
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {                                   // QK 12..15: V reads 0..7
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        for (int i = 0; i < 16; ++i) {             // P V MFMA i
+            const shortx8 vv = __builtin_shufflevector(vlo[i], vhi[i], 0, 1, 2, 3, 4, 5, 6, 7);
+            const int sg = i >> 2, db = i & 3;
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vv), pf[sg >> 1][sg & 1],
+                                                             o[db], 0, 0, 0);
+            if (i + 4 < 16) read_v(i + 4);
+            __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int j = 0; j < 12; ++j) {                                  // PV 0..11: V reads 8..31
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);              // PV 12..15
     };
 
     // online softmax of this lane's query row (the other half of the row is 32 lanes away).
@@ -481,12 +473,16 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
 }
 
 bool launch_engine_bf16_pp(const EngineArgs& ea, unsigned grid, hipStream_t st) {
-    if (ea.flags == (kEngAnchorRegion | kEngDense | kEngStoreOut))
-        hipLaunchKernelGGL(engine_bf16_pp_kernel<(kEngAnchorRegion | kEngDense | kEngStoreOut)>, dim3(grid), dim3(512),
-                           0, st, ea);
-    else
+    switch (ea.flags) {
+#define AA_ENGINE_CASE(F) \
+    case (F): hipLaunchKernelGGL(engine_bf16_pp_kernel<(F)>, dim3(grid), dim3(512), 0, st, ea); return true;
+    AA_ENGINE_CASE(kEngList | kEngLoadState | kEngStoreOut)           // stage 3 from the cached state
+    AA_ENGINE_CASE(kEngAnchorRegion | kEngDense | kEngStoreOut)       // dense causal attention
+#undef AA_ENGINE_CASE
+    default:                                                          // any other mode: flags read at run time
         hipLaunchKernelGGL(engine_bf16_pp_kernel<-1>, dim3(grid), dim3(512), 0, st, ea);
-    return true;
+        return true;
+    }
 }
 
 }  // namespace aa
