@@ -11,7 +11,9 @@
  *    `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *  * The library never allocates, frees or keeps device memory and never
  *    synchronises the stream: calls only enqueue kernels.  The caller keeps all
- *    buffers alive until the stream has run them.
+ *    buffers alive until the stream has run them.  Calls keep no state between
+ *    them: concurrent calls from several host threads are safe as long as they
+ *    write to different buffers (and workspaces).
  *  * Return value: 0 on success, a negative AA_E* code otherwise.  All argument
  *    checks run on the host before anything is enqueued, so a failing call has
  *    no effect on the device.  anchor_strerror() names a code.
@@ -63,6 +65,7 @@ extern "C" {
 
 enum { AA_FP32 = 0, AA_BF16 = 1 };
 enum { AA_STRIPE = 0, AA_BLOCK = 1 };   /* identification granularity (b_q, 1) or (b_q, b_kv) */
+enum { AA_ENGINE_AUTO = 0, AA_ENGINE_128 = 1, AA_ENGINE_256 = 2 };
 
 enum {
     AA_OK = 0,
@@ -89,6 +92,13 @@ typedef struct aa_params {
     int32_t use_anchor;       /* 1; 0 = compare against a zero anchor (Table 4, "without")      */
     int32_t granularity;      /* AA_STRIPE (0): one decision per key column, the method's own;    */
                               /* AA_BLOCK (1): one decision per key block (see stripe_select)    */
+    int32_t engine;           /* which bf16 tile engine runs stages 1, 3 and dense attention.    */
+                              /* AA_ENGINE_AUTO (0): chosen per launch (by length for dense       */
+                              /* attention, on the device by the mean list length for stage 3);   */
+                              /* AA_ENGINE_128 / AA_ENGINE_256: the engine with 128 / 256 query   */
+                              /* rows per work-group (256 needs dense attention or an even step,  */
+                              /* falls back to 128 otherwise).  Results agree to rounding.  A     */
+                              /* testing / tuning aid, not part of the method; ignored for fp32.  */
     int64_t q_stride[3], k_stride[3], v_stride[3], o_stride[3]; /* batch, head, token; elements */
     const int32_t *cu_seqlens;/* device int32[B+1] or NULL                                      */
     int64_t total_tokens;     /* cu_seqlens[B]; ignored when cu_seqlens == NULL                 */
@@ -108,17 +118,14 @@ typedef struct aa_sizes {
 } aa_sizes;
 
 /*
- * Tuning / testing aid, not part of the method: which of the two bf16 tile engines the
- * following calls of this process use.  0 (default): chosen per launch (by sequence length for
- * dense attention, on the device by the mean list length for stage 3, always the 128-row engine
- * for stage 1); 1: the engine with 128 query rows per work-group; 2: the engine with 256 query
- * rows per work-group wherever it applies (dense attention, even step).  Results agree to
- * rounding.  Not thread-safe against concurrent calls.  AA_EINVAL for other values.
+ * Validates params (AA_EINVAL / AA_EUNSUPPORTED) and fills *out.  Host only.  Buffer
+ * arithmetic of this library, not an operation of the paper.  idx_capacity_max holds for
+ * every split of total_tokens into B sequences of at most N tokens.
  */
-int anchor_set_engine(int mode);
-
-/* Validates params (AA_EINVAL / AA_EUNSUPPORTED) and fills *out.  Host only. */
 int anchor_sizes(const aa_params *params, aa_sizes *out);
+
+/* *bytes_out = aa_sizes.prefill_ws_bytes, the workspace of anchor_attention_prefill.  Host only. */
+int anchor_workspace_bytes(const aa_params *params, size_t *bytes_out);
 
 /*
  * Stage 1, pattern-based anchor computation (Sec. 3.1, Eq. 1; Algorithm 1).
@@ -136,8 +143,10 @@ int anchor_compute(const aa_params *params, const void *q, const void *k, const 
  * some block i of the group has  xa_pooled_i - scale*<mean of block i's queries, k_j> <= theta.
  * Writes counts[groups], offsets[groups+1] (int64, see Layouts), and the lists.
  * If the lists (with padding) need more than idx_capacity entries, *overflow_flag
- * is set to 1, nothing is written past the capacity, and offsets stay exact;
- * otherwise it is set to 0.  ws: select_ws_bytes of scratch.
+ * is set to 1, nothing is written past the capacity, and offsets stay exact
+ * (offsets[groups] is the capacity that would have sufficed); the lists are then
+ * incomplete and must not be attended.  Otherwise the flag is set to 0.
+ * ws: select_ws_bytes of scratch.
  *
  * granularity = AA_BLOCK switches to the block granularity that Sec. 2.1.2 /
  * Table 1 set against stripes: the same difference test, taken once per key block
@@ -157,22 +166,32 @@ int stripe_select(const aa_params *params, const void *q, const void *k, const f
  * K/V rows of its group's list, out = acc / l.  If M, L and Acc are all NULL the
  * anchor region is computed inside the kernel instead of being read.  lse
  * (nullable) receives log sum_{P(r)} exp S(r,j).
+ * counts / offsets / idx are stripe_select's outputs, idx_capacity the entries idx
+ * holds.  The kernels never read idx at or beyond idx_capacity: if the lists do not
+ * fit (offsets[groups] > idx_capacity, the case stripe_select flags as overflow)
+ * the call writes nothing to out and lse.
  */
 int sparse_attn(const aa_params *params, const void *q, const void *k, const void *v,
                 const float *M, const float *L, const float *Acc,
                 const int32_t *counts, const int64_t *offsets, const int32_t *idx,
-                void *out, float *lse, void *stream);
+                int64_t idx_capacity, void *out, float *lse, void *stream);
 
 /*
- * The whole prefill path: stage 1 -> 2 -> 3 on one stream, intermediates in ws
- * (prefill_ws_bytes).  stats (nullable, device int64[4]) receives
- * { attended (q,k) pairs, total selected list entries, 0, 0 }.
+ * The whole prefill path of Section 3 (Algorithm 1 -> 2 -> 3, with the step rule of
+ * Sec. 3.4): anchor_compute, stripe_select and sparse_attn on one stream, intermediates
+ * in ws (prefill_ws_bytes, see anchor_workspace_bytes; its index region holds
+ * idx_capacity_max entries, so the lists always fit).  stats (nullable, device int64[4])
+ * receives { attended (q,k) pairs, total selected list entries, 0, 0 }.
  */
 int anchor_attention_prefill(const aa_params *params, const void *q, const void *k, const void *v,
                              void *out, float *lse, int64_t *stats,
                              void *ws, size_t ws_bytes, void *stream);
 
-/* Exact causal attention with the same tile engine (comparator; theta=+inf target). */
+/*
+ * Exact causal softmax attention with the same tile engine.  Not an operation of the
+ * paper's method: the same-GPU comparator the speedup is quoted against, and what the
+ * method must reproduce at theta = +inf.
+ */
 int dense_causal_flash(const aa_params *params, const void *q, const void *k, const void *v,
                        void *out, float *lse, void *stream);
 

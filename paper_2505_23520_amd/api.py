@@ -15,10 +15,11 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("ANCHOR_ATTENTION_LIB", os.path.join(_HERE, "libanchor_attention.so"))
+LIB_PATH = os.path.join(_HERE, "libanchor_attention.so")
 
 AA_FP32, AA_BF16 = 0, 1
 AA_STRIPE, AA_BLOCK = 0, 1
+AA_ENGINE_AUTO, AA_ENGINE_128, AA_ENGINE_256 = 0, 1, 2
 AA_OK, AA_EINVAL, AA_EUNSUPPORTED, AA_EWORKSPACE, AA_EHIP = 0, -1, -2, -3, -4
 
 
@@ -30,7 +31,7 @@ class aa_params(ctypes.Structure):
         ("n_init", ctypes.c_int32), ("window", ctypes.c_int32), ("step", ctypes.c_int32),
         ("theta", ctypes.c_float), ("softmax_scale", ctypes.c_float),
         ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32), ("use_anchor", ctypes.c_int32),
-        ("granularity", ctypes.c_int32),
+        ("granularity", ctypes.c_int32), ("engine", ctypes.c_int32),
         ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
         ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
         ("cu_seqlens", ctypes.c_void_p), ("total_tokens", ctypes.c_int64),
@@ -46,37 +47,37 @@ class aa_sizes(ctypes.Structure):
     ]
 
 
-if not os.path.exists(LIB_PATH):
-    raise ImportError(
-        "libanchor_attention.so is not built (%s). Build it with "
-        "`python -m paper_2505_23520_amd.build`; there is no fallback path." % LIB_PATH)
-_lib = ctypes.CDLL(LIB_PATH)
-
 _P = ctypes.c_void_p
 _PP = ctypes.POINTER(aa_params)
-_lib.anchor_sizes.restype = ctypes.c_int
-_lib.anchor_sizes.argtypes = [_PP, ctypes.POINTER(aa_sizes)]
-_lib.anchor_compute.restype = ctypes.c_int
-_lib.anchor_compute.argtypes = [_PP, _P, _P, _P, _P, _P, _P, _P, _P]
-_lib.stripe_select.restype = ctypes.c_int
-_lib.stripe_select.argtypes = [_PP, _P, _P, _P, _P, _P, _P, ctypes.c_int64, _P, _P, ctypes.c_size_t, _P]
-_lib.sparse_attn.restype = ctypes.c_int
-_lib.sparse_attn.argtypes = [_PP, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P]
-_lib.anchor_attention_prefill.restype = ctypes.c_int
-_lib.anchor_attention_prefill.argtypes = [_PP, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, _P]
-_lib.dense_causal_flash.restype = ctypes.c_int
-_lib.dense_causal_flash.argtypes = [_PP, _P, _P, _P, _P, _P, _P]
-_lib.anchor_probe_mfma.restype = ctypes.c_int
-_lib.anchor_probe_mfma.argtypes = [ctypes.c_int, _P, _P]
-_lib.anchor_set_engine.restype = ctypes.c_int
-_lib.anchor_set_engine.argtypes = [ctypes.c_int]
-_lib.anchor_strerror.restype = ctypes.c_char_p
-_lib.anchor_strerror.argtypes = [ctypes.c_int]
-_lib.anchor_last_hip_error.restype = ctypes.c_char_p
-_lib.anchor_last_hip_error.argtypes = []
+_SIGNATURES = {
+    "anchor_sizes": (ctypes.c_int, [_PP, ctypes.POINTER(aa_sizes)]),
+    "anchor_workspace_bytes": (ctypes.c_int, [_PP, ctypes.POINTER(ctypes.c_size_t)]),
+    "anchor_compute": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, _P, _P]),
+    "stripe_select": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, ctypes.c_int64, _P, _P, ctypes.c_size_t, _P]),
+    "sparse_attn": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int64, _P, _P, _P]),
+    "anchor_attention_prefill": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, _P]),
+    "dense_causal_flash": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P]),
+    "anchor_probe_mfma": (ctypes.c_int, [ctypes.c_int, _P, _P]),
+    "anchor_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "anchor_last_hip_error": (ctypes.c_char_p, []),
+}
+EXPORTS = tuple(_SIGNATURES)
 
-EXPORTS = ("anchor_set_engine", "anchor_sizes", "anchor_compute", "stripe_select", "sparse_attn", "anchor_attention_prefill",
-           "dense_causal_flash", "anchor_probe_mfma", "anchor_strerror", "anchor_last_hip_error")
+
+def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
+    """dlopen the built library and declare its signatures; ImportError if it is not there."""
+    if not os.path.exists(path):
+        raise ImportError(
+            "libanchor_attention.so is not built (%s). Build it with "
+            "`python -m paper_2505_23520_amd.build`; there is no fallback path." % path)
+    lib = ctypes.CDLL(path)
+    for name, (res, args) in _SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+_lib = load_library()
 
 
 class AnchorError(RuntimeError):
@@ -115,6 +116,7 @@ class Config:
     use_anchor: bool = True
     causal: bool = True
     granularity: int = AA_STRIPE     # AA_BLOCK: one decision per key block (Sec. 2.1.2, Table 1)
+    engine: int = AA_ENGINE_AUTO     # testing / tuning aid: force one of the two bf16 tile engines
 
 
 def _strides(t: torch.Tensor, packed: bool):
@@ -146,6 +148,7 @@ def make_params(cfg: Config, q, k, v, out=None, cu_seqlens=None, max_seqlen=None
     p.theta, p.softmax_scale = cfg.theta, cfg.softmax_scale
     p.causal, p.use_anchor = int(cfg.causal), int(cfg.use_anchor)
     p.granularity = int(cfg.granularity)
+    p.engine = int(cfg.engine)
     p.dtype = {torch.float32: AA_FP32, torch.bfloat16: AA_BF16}[q.dtype]
     o = q if out is None else out
     for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", o)):
@@ -157,6 +160,12 @@ def anchor_sizes(p: aa_params) -> aa_sizes:
     s = aa_sizes()
     _check(_lib.anchor_sizes(ctypes.byref(p), ctypes.byref(s)))
     return s
+
+
+def anchor_workspace_bytes(p: aa_params) -> int:
+    n = ctypes.c_size_t(0)
+    _check(_lib.anchor_workspace_bytes(ctypes.byref(p), ctypes.byref(n)))
+    return int(n.value)
 
 
 def anchor_compute(p, q, k, v, M, L, Acc, xa_pooled, stream=None):
@@ -171,9 +180,10 @@ def stripe_select(p, q, k, xa_pooled, counts, offsets, idx, overflow_flag, ws, s
                               0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
 
 
-def sparse_attn(p, q, k, v, M, L, Acc, counts, offsets, idx, out, lse=None, stream=None):
+def sparse_attn(p, q, k, v, M, L, Acc, counts, offsets, idx, out, lse=None, stream=None, idx_capacity=None):
+    cap = idx.numel() if idx_capacity is None else idx_capacity
     _check(_lib.sparse_attn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(M), _ptr(L), _ptr(Acc), _ptr(counts),
-                            _ptr(offsets), _ptr(idx), _ptr(out), _ptr(lse), _stream(stream)))
+                            _ptr(offsets), _ptr(idx), cap, _ptr(out), _ptr(lse), _stream(stream)))
 
 
 def anchor_attention_prefill(p, q, k, v, out, lse, stats, ws, stream=None):
@@ -185,11 +195,6 @@ def anchor_attention_prefill(p, q, k, v, out, lse, stats, ws, stream=None):
 def dense_causal_flash(p, q, k, v, out, lse=None, stream=None):
     _check(_lib.dense_causal_flash(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
                                    _stream(stream)))
-
-
-def anchor_set_engine(mode: int):
-    """0: engine chosen per launch; 1 / 2: force the 128-row / 256-row bf16 engine (testing aid)."""
-    _check(_lib.anchor_set_engine(int(mode)))
 
 
 def anchor_probe_mfma(iters, scratch, stream=None):

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/anchor_attention.h"
 #include "aa_common.h"
@@ -16,7 +17,6 @@ namespace aa {
 namespace {
 
 thread_local char g_hip_err[256] = "";
-int g_engine_mode = 0;   // anchor_set_engine
 
 int hip_fail(hipError_t e, const char* what) {
     snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
@@ -27,10 +27,11 @@ int hip_fail(hipError_t e, const char* what) {
         hipError_t e_ = (call);                              \
         if (e_ != hipSuccess) return hip_fail(e_, #call);    \
     } while (0)
-#define AA_LAUNCHED(name)                                    \
+// AA_LAUNCH(kernel, grid, block, lds bytes, stream, args...): the launch's own status
+#define AA_LAUNCH(kern, ...)                                 \
     do {                                                     \
-        hipError_t e_ = hipGetLastError();                   \
-        if (e_ != hipSuccess) return hip_fail(e_, name);     \
+        hipError_t e_ = launch_kernel(kern, __VA_ARGS__);    \
+        if (e_ != hipSuccess) return hip_fail(e_, #kern);    \
     } while (0)
 
 inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
@@ -45,11 +46,12 @@ struct Plan {
     size_t pf_M, pf_L, pf_Acc, pf_xa, pf_counts, pf_offsets, pf_flag, pf_idx, pf_sel;  // prefill workspace
 };
 
-// candidates of one sequence of `len` tokens, each group's count rounded up to a list chunk
-long long padded_candidates(const aa_params* p, long long len) {
+// candidates of the first `ngroups` groups of a sequence, each group's count rounded up to a list
+// chunk (a group's candidate range depends on its index alone, not on the sequence's length)
+long long padded_candidates(const aa_params* p, long long ngroups) {
     const long long span = (long long)p->block_q * p->step;
     long long tot = 0;
-    for (long long g = 0; g * span < len; ++g) {
+    for (long long g = 0; g < ngroups; ++g) {
         long long W = g * span - p->window;
         if (W < p->n_init) W = p->n_init;
         tot += cdiv(W - p->n_init, kIdxPad) * kIdxPad;
@@ -67,9 +69,13 @@ int make_plan(const aa_params* p, Plan* pl) {
     if (p->dtype != AA_FP32 && p->dtype != AA_BF16) return AA_EINVAL;
     if (p->granularity != AA_STRIPE && p->granularity != AA_BLOCK) return AA_EINVAL;
     if (p->granularity == AA_BLOCK && (p->n_init % p->block_kv || p->window % p->block_kv)) return AA_EINVAL;
+    if (p->engine != AA_ENGINE_AUTO && p->engine != AA_ENGINE_128 && p->engine != AA_ENGINE_256) return AA_EINVAL;
     if (p->cu_seqlens && (p->total_tokens <= 0 || p->N > p->total_tokens)) return AA_EINVAL;
     if (p->causal != 1) return AA_EUNSUPPORTED;
     if (p->step > 128) return AA_EUNSUPPORTED;
+    // the block-granularity mask kernel keeps a group's pooled rows and one flag per key block in LDS
+    if (p->granularity == AA_BLOCK && mask_block_lds_bytes(p->N, p->d, p->block_q, p->step) > kMaskBlockLdsMax)
+        return AA_EUNSUPPORTED;
     const int vec = p->dtype == AA_BF16 ? 8 : 4;             // elements per 16-byte access
     if (p->dtype == AA_BF16) {
         if (p->d != 128 || p->block_q != 128) return AA_EUNSUPPORTED;
@@ -117,18 +123,22 @@ int make_plan(const aa_params* p, Plan* pl) {
         s.grp_cap = p->total_tokens / span + p->B;
         s.blocks = (int64_t)p->Hq * s.blk_cap;
         s.groups = (int64_t)p->Hq * s.grp_cap;
-        // lists grow faster than linearly with the length, so the worst split of total_tokens
-        // into sequences of at most N tokens is as many full-length sequences as fit
-        const long long full = p->total_tokens / p->N, rest = p->total_tokens % p->N;
-        s.idx_capacity_max = (int64_t)p->Hq * (full * padded_candidates(p, p->N) + padded_candidates(p, rest) +
-                                               (long long)kIdxPad * s.grp_cap);
+        // Worst split of total_tokens into B sequences of at most N tokens.  A group counts in full
+        // as soon as it has one row, so the bound goes over group counts: the sequences have at most
+        // gtot groups together and at most ngrp_max each, and the candidates of a sequence with n
+        // groups, F(n), are convex in n (later groups have longer candidate ranges): the maximum of
+        // sum F(n_b) puts as many sequences as possible at ngrp_max and the remainder into one more.
+        long long gtot = p->total_tokens / span + p->B;
+        if (gtot > (long long)p->B * k.ngrp_max) gtot = (long long)p->B * k.ngrp_max;
+        s.idx_capacity_max = (int64_t)p->Hq * ((gtot / k.ngrp_max) * padded_candidates(p, k.ngrp_max) +
+                                               padded_candidates(p, gtot % k.ngrp_max));
     } else {
         s.rows = (int64_t)p->B * p->Hq * p->N;
         s.blk_cap = k.nblk_max;
         s.grp_cap = k.ngrp_max;
         s.blocks = (int64_t)p->B * p->Hq * s.blk_cap;
         s.groups = (int64_t)p->B * p->Hq * s.grp_cap;
-        s.idx_capacity_max = (int64_t)p->B * p->Hq * padded_candidates(p, p->N);
+        s.idx_capacity_max = (int64_t)p->B * p->Hq * padded_candidates(p, k.ngrp_max);
     }
     if (s.idx_capacity_max < kIdxPad) s.idx_capacity_max = kIdxPad;
     s.acc_elems = s.rows * p->d;
@@ -166,51 +176,61 @@ int make_plan(const aa_params* p, Plan* pl) {
 
 bool misaligned(const void* ptr) { return ((uintptr_t)ptr & 15) != 0; }
 
-int launch_engine(const Plan& pl, int dtype, EngineArgs& ea, hipStream_t st) {
+// kernels that ask for more dynamic LDS than the default limit: raised once per process
+std::once_flag g_attr_once;
+hipError_t g_attr_status = hipSuccess;
+hipError_t raise_lds_limits() {
+    std::call_once(g_attr_once, [] {
+        g_attr_status = hipFuncSetAttribute((const void*)engine_fp32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)engine_fp32_lds_bytes(128, 128));
+        if (g_attr_status == hipSuccess)
+            g_attr_status = hipFuncSetAttribute((const void*)mask_block_kernel,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaskBlockLdsMax);
+    });
+    return g_attr_status;
+}
+
+int engine_status(int rc, const char* name) {
+    if (rc < 0) return AA_EUNSUPPORTED;
+    return rc == (int)hipSuccess ? AA_OK : hip_fail((hipError_t)rc, name);
+}
+
+int launch_engine(const Plan& pl, const aa_params* prm, EngineArgs& ea, hipStream_t st) {
     const KParams& k = pl.kp;
     const unsigned grid = (unsigned)((long long)k.nblk_max * k.Hq * k.B);
-    if (dtype == AA_BF16) {
+    ea.groups_total = pl.sz.groups;
+    ea.sel = 0;
+    if (prm->dtype == AA_BF16) {
         // Two bf16 engines: 128 query rows per work-group (two work-groups per CU) and 256 rows
         // per work-group with the MFMA / softmax phases of the two waves of a SIMD alternating.
         // The second is faster on long tile loops and slower on short ones (its prologue and
         // epilogue overlap with nothing); it needs both blocks of a pair to share window and list.
         const bool pair_ok = (ea.flags & kEngDense) || k.step % 2 == 0;
-        int choice = g_engine_mode;                 // 0 auto, 1: 128 rows, 2: 256 rows
-        if (!pair_ok) choice = 1;
-        ea.sel = 0;
-        if (choice == 0) {
+        int choice = prm->engine;                   // 0 auto, 1: 128 rows, 2: 256 rows
+        if (!pair_ok) choice = AA_ENGINE_128;
+        if (choice == AA_ENGINE_AUTO) {
             if (ea.flags & kEngList) choice = 3;    // decided on the device from the list lengths
-            else if (ea.flags & kEngDense) choice = k.N >= 8192 ? 2 : 1;
-            else choice = 1;                        // anchor region alone: at most step + 3 blocks of keys
+            else if (ea.flags & kEngDense) choice = k.N >= 8192 ? AA_ENGINE_256 : AA_ENGINE_128;
+            else choice = AA_ENGINE_128;            // anchor region alone: at most step + 3 blocks of keys
         }
         const unsigned gridp = (unsigned)((long long)((k.nblk_max + 1) / 2) * k.Hq * k.B);
+        int rc = AA_OK;
         if (choice == 3) {
-            ea.sel_groups = pl.sz.groups;
             ea.sel_entries = 48ll * 64 * pl.sz.groups;   // mean list of 48 tiles
             ea.sel = 1;
-            if (!launch_engine_bf16(ea, grid, st)) return AA_EUNSUPPORTED;
-            AA_LAUNCHED("engine_bf16_kernel");
+            rc = engine_status(launch_engine_bf16(ea, grid, st), "engine_bf16_kernel");
+            if (rc != AA_OK) return rc;
             ea.sel = 2;
-            if (!launch_engine_bf16_pp(ea, gridp, st)) return AA_EUNSUPPORTED;
-            AA_LAUNCHED("engine_bf16_pp_kernel");
-        } else if (choice == 2) {
-            if (!launch_engine_bf16_pp(ea, gridp, st)) return AA_EUNSUPPORTED;
-            AA_LAUNCHED("engine_bf16_pp_kernel");
+            rc = engine_status(launch_engine_bf16_pp(ea, gridp, st), "engine_bf16_pp_kernel");
+        } else if (choice == AA_ENGINE_256) {
+            rc = engine_status(launch_engine_bf16_pp(ea, gridp, st), "engine_bf16_pp_kernel");
         } else {
-            if (!launch_engine_bf16(ea, grid, st)) return AA_EUNSUPPORTED;
-            AA_LAUNCHED("engine_bf16_kernel");
+            rc = engine_status(launch_engine_bf16(ea, grid, st), "engine_bf16_kernel");
         }
-    } else {
-        const size_t lds = engine_fp32_lds_bytes(k.d, k.bq);
-        static bool attr_set32 = false;
-        if (!attr_set32) {
-            AA_HIP(hipFuncSetAttribute((const void*)engine_fp32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)engine_fp32_lds_bytes(128, 128)));
-            attr_set32 = true;
-        }
-        hipLaunchKernelGGL(engine_fp32_kernel, dim3(grid), dim3(2 * k.bq), lds, st, ea);
-        AA_LAUNCHED("engine_fp32_kernel");
+        return rc;
     }
+    AA_HIP(raise_lds_limits());
+    AA_LAUNCH(engine_fp32_kernel, dim3(grid), dim3(2 * k.bq), engine_fp32_lds_bytes(k.d, k.bq), st, ea);
     return AA_OK;
 }
 
@@ -222,7 +242,7 @@ int run_anchor(const Plan& pl, const aa_params* p, const void* q, const void* k,
     ea.flags = kEngAnchorRegion | kEngStoreState;
     ea.q = q; ea.k = k; ea.v = v;
     ea.Mout = M; ea.Lout = L; ea.Accout = Acc; ea.xa = xa;
-    return launch_engine(pl, p->dtype, ea, st);
+    return launch_engine(pl, p, ea, st);
 }
 
 int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k, const float* xa, int32_t* counts,
@@ -244,57 +264,38 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     sa.groups_total = pl.sz.groups;
 
     const dim3 gblk(kp.nblk_max, kp.Hq, kp.B), ggrp(kp.ngrp_max, kp.Hq, kp.B);
-    if (kp.packed) {
-        hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)cdiv(pl.sz.groups, 256)), dim3(256), 0, st, counts,
-                           (long long)pl.sz.groups);
-        AA_LAUNCHED("zero_i32_kernel");
-    }
+    if (p->granularity == AA_BLOCK) AA_HIP(raise_lds_limits());   // before anything is enqueued
+    if (kp.packed)
+        AA_LAUNCH(zero_i32_kernel, dim3((unsigned)cdiv(pl.sz.groups, 256)), dim3(256), 0, st, counts,
+                  (long long)pl.sz.groups);
     if (p->granularity == AA_BLOCK) {
         if (p->dtype == AA_BF16)
-            hipLaunchKernelGGL(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
+            AA_LAUNCH(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
         else
-            hipLaunchKernelGGL(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);
-        AA_LAUNCHED("pool_q kernel");
-        hipLaunchKernelGGL(pool_k_kernel, dim3(kp.nblk_max, kp.Hkv, kp.B), dim3(256), 0, st, sa);
-        AA_LAUNCHED("pool_k_kernel");
-        static bool attr_set_blk = false;
-        if (!attr_set_blk) {
-            AA_HIP(hipFuncSetAttribute((const void*)mask_block_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       128 * 1024));
-            attr_set_blk = true;
-        }
-        const size_t lds = mask_block_lds_bytes(kp.N, kp.d, kp.bq, kp.step);
-        if (lds > 128 * 1024) return AA_EUNSUPPORTED;
-        hipLaunchKernelGGL(mask_block_kernel, ggrp, dim3(256), lds, st, sa);
-        AA_LAUNCHED("mask_block_kernel");
+            AA_LAUNCH(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);
+        AA_LAUNCH(pool_k_kernel, dim3(kp.nblk_max, kp.Hkv, kp.B), dim3(256), 0, st, sa);
+        AA_LAUNCH(mask_block_kernel, ggrp, dim3(256), mask_block_lds_bytes(kp.N, kp.d, kp.bq, kp.step), st, sa);
     } else if (p->dtype == AA_BF16) {
-        hipLaunchKernelGGL(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
-        AA_LAUNCHED("pool_q_bf16_kernel");
+        AA_LAUNCH(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
         // row tiles are folded in pairs (short with long); the longest sequence bounds every other
         const int ny = (int)cdiv(kp.nblk_max, mask_row_tile(kp.step));
         const dim3 gm((unsigned)mask_grid_x(kp.nblk_max, kp.step, kp.bq, kp.w, kp.n_init),
                       (unsigned)((ny + 1) / 2), (unsigned)(kp.B * kp.Hq));
-        hipLaunchKernelGGL(mask_bf16_kernel, gm, dim3(256), 0, st, sa);
-        AA_LAUNCHED("mask_bf16_kernel");
+        AA_LAUNCH(mask_bf16_kernel, gm, dim3(256), 0, st, sa);
     } else {
-        hipLaunchKernelGGL(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);
-        AA_LAUNCHED("pool_q_fp32_kernel");
+        AA_LAUNCH(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);
         const dim3 gm((unsigned)cdiv(kp.N, 256), (unsigned)kp.ngrp_max, (unsigned)(kp.B * kp.Hq));
-        hipLaunchKernelGGL(mask_fp32_kernel, gm, dim3(256), (size_t)kp.step * kp.d * 4, st, sa);
-        AA_LAUNCHED("mask_fp32_kernel");
+        AA_LAUNCH(mask_fp32_kernel, gm, dim3(256), (size_t)kp.step * kp.d * 4, st, sa);
     }
-    hipLaunchKernelGGL(count_kernel, ggrp, dim3(256), 0, st, sa);
-    AA_LAUNCHED("count_kernel");
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), 0, st, sa);
-    AA_LAUNCHED("scan_kernel");
-    hipLaunchKernelGGL(fill_kernel, dim3(kp.ngrp_max, (unsigned)cdiv(sa.nseg, 4), kp.Hq * kp.B), dim3(256), 0, st, sa);
-    AA_LAUNCHED("fill_kernel");
+    AA_LAUNCH(count_kernel, ggrp, dim3(256), 0, st, sa);
+    AA_LAUNCH(scan_kernel, dim3(1), dim3(1024), 0, st, sa);
+    AA_LAUNCH(fill_kernel, dim3(kp.ngrp_max, (unsigned)cdiv(sa.nseg, 4), kp.Hq * kp.B), dim3(256), 0, st, sa);
     return AA_OK;
 }
 
 int run_sparse(const Plan& pl, const aa_params* p, const void* q, const void* k, const void* v, const float* M,
                const float* L, const float* Acc, const int32_t* counts, const int64_t* offsets, const int32_t* idx,
-               void* out, float* lse, hipStream_t st) {
+               int64_t idx_capacity, void* out, float* lse, hipStream_t st) {
     EngineArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.p = pl.kp;
@@ -302,8 +303,9 @@ int run_sparse(const Plan& pl, const aa_params* p, const void* q, const void* k,
     ea.q = q; ea.k = k; ea.v = v;
     ea.Min = M; ea.Lin = L; ea.Accin = Acc;
     ea.counts = counts; ea.offsets = (const long long*)offsets; ea.idx = idx;
+    ea.idx_capacity = idx_capacity;
     ea.out = out; ea.lse = lse;
-    return launch_engine(pl, p->dtype, ea, st);
+    return launch_engine(pl, p, ea, st);
 }
 
 // stats[0] += attended pairs, stats[1] += selected entries.  grid (ngrp_max, Hq, B), 64 threads.
@@ -356,18 +358,21 @@ using namespace aa;
 
 extern "C" {
 
-int anchor_set_engine(int mode) {
-    if (mode < 0 || mode > 2) return AA_EINVAL;
-    g_engine_mode = mode;
-    return AA_OK;
-}
-
 int anchor_sizes(const aa_params* params, aa_sizes* out) {
     Plan pl;
     int rc = make_plan(params, &pl);
     if (rc != AA_OK) return rc;
     if (!out) return AA_EINVAL;
     *out = pl.sz;
+    return AA_OK;
+}
+
+int anchor_workspace_bytes(const aa_params* params, size_t* bytes_out) {
+    Plan pl;
+    int rc = make_plan(params, &pl);
+    if (rc != AA_OK) return rc;
+    if (!bytes_out) return AA_EINVAL;
+    *bytes_out = pl.sz.prefill_ws_bytes;
     return AA_OK;
 }
 
@@ -395,17 +400,18 @@ int stripe_select(const aa_params* params, const void* q, const void* k, const f
 }
 
 int sparse_attn(const aa_params* params, const void* q, const void* k, const void* v, const float* M, const float* L,
-                const float* Acc, const int32_t* counts, const int64_t* offsets, const int32_t* idx, void* out,
-                float* lse, void* stream) {
+                const float* Acc, const int32_t* counts, const int64_t* offsets, const int32_t* idx,
+                int64_t idx_capacity, void* out, float* lse, void* stream) {
     Plan pl;
     int rc = make_plan(params, &pl);
     if (rc != AA_OK) return rc;
-    if (!q || !k || !v || !counts || !offsets || !idx || !out) return AA_EINVAL;
+    if (!q || !k || !v || !counts || !offsets || !idx || !out || idx_capacity < 0) return AA_EINVAL;
     const int nstate = (M != nullptr) + (L != nullptr) + (Acc != nullptr);
     if (nstate != 0 && nstate != 3) return AA_EINVAL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(idx) || misaligned(Acc))
         return AA_EINVAL;
-    return run_sparse(pl, params, q, k, v, M, L, Acc, counts, offsets, idx, out, lse, (hipStream_t)stream);
+    return run_sparse(pl, params, q, k, v, M, L, Acc, counts, offsets, idx, idx_capacity, out, lse,
+                      (hipStream_t)stream);
 }
 
 int anchor_attention_prefill(const aa_params* params, const void* q, const void* k, const void* v, void* out,
@@ -430,14 +436,12 @@ int anchor_attention_prefill(const aa_params* params, const void* q, const void*
     if (rc != AA_OK) return rc;
     rc = run_select(pl, params, q, k, xa, counts, offsets, idx, pl.sz.idx_capacity_max, flag, w + pl.pf_sel, st);
     if (rc != AA_OK) return rc;
-    rc = run_sparse(pl, params, q, k, v, M, L, Acc, counts, offsets, idx, out, lse, st);
+    rc = run_sparse(pl, params, q, k, v, M, L, Acc, counts, offsets, idx, pl.sz.idx_capacity_max, out, lse, st);
     if (rc != AA_OK) return rc;
     if (stats) {
-        hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)stats, 4);
-        AA_LAUNCHED("zero_u64_kernel");
-        hipLaunchKernelGGL(stats_kernel, dim3(pl.kp.ngrp_max, pl.kp.Hq, pl.kp.B), dim3(64), 0, st, pl.kp, counts,
-                           (unsigned long long*)stats);
-        AA_LAUNCHED("stats_kernel");
+        AA_LAUNCH(zero_u64_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)stats, 4);
+        AA_LAUNCH(stats_kernel, dim3(pl.kp.ngrp_max, pl.kp.Hq, pl.kp.B), dim3(64), 0, st, pl.kp, (const int*)counts,
+                  (unsigned long long*)stats);
     }
     return AA_OK;
 }
@@ -455,13 +459,12 @@ int dense_causal_flash(const aa_params* params, const void* q, const void* k, co
     ea.flags = kEngAnchorRegion | kEngDense | kEngStoreOut;
     ea.q = q; ea.k = k; ea.v = v;
     ea.out = out; ea.lse = lse;
-    return launch_engine(pl, params->dtype, ea, (hipStream_t)stream);
+    return launch_engine(pl, params, ea, (hipStream_t)stream);
 }
 
 int anchor_probe_mfma(int iters, void* scratch, void* stream) {
     if (iters <= 0 || !scratch) return AA_EINVAL;
-    hipLaunchKernelGGL(probe_mfma_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream, iters, (float*)scratch);
-    AA_LAUNCHED("probe_mfma_kernel");
+    AA_LAUNCH(probe_mfma_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream, iters, (float*)scratch);
     return AA_OK;
 }
 

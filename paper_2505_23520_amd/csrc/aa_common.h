@@ -10,6 +10,16 @@ namespace aa {
 constexpr int kLane = 64;          // wavefront width on CDNA4
 constexpr int kIdxPad = 64;        // list chunks are 64 entries (one K/V tile)
 
+// Launch with the launch's own status as return value (hipGetLastError() after a <<<>>> launch
+// would also report, and clear, an error some earlier and unrelated call left behind).
+template <class T> struct arg_of { using type = T; };
+template <class... KArgs>
+inline hipError_t launch_kernel(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st,
+                                typename arg_of<KArgs>::type... args) {
+    void* ptrs[] = {(void*)&args...};
+    return hipLaunchKernel((const void*)kern, grid, block, ptrs, lds, st);
+}
+
 // Kernel-side copy of the call's parameters (plain data, passed by value).
 struct KParams {
     int B, Hq, Hkv, N, d;

@@ -24,24 +24,30 @@ struct EngineArgs {
     float *Mout, *Lout, *Accout, *xa;
     void* out;
     float* lse;
-    // Two engines can be launched for the same list-driven call; each decides on the device from
-    // the total (padded) list length offsets[sel_groups] whether it is the one to run:
-    // sel = 0 runs always, sel = 1 runs iff the total is below sel_entries, sel = 2 iff not.
+    // List-driven calls: offsets[groups_total] is the total (padded) list length.  Lists that do not
+    // fit the caller's idx buffer (idx_capacity entries) are incomplete: the launch then does nothing.
+    // Two engines can be launched for the same list-driven call; each decides on the device from that
+    // total whether it is the one to run: sel = 0 runs always, sel = 1 runs iff the total is below
+    // sel_entries, sel = 2 iff not.
+    long long groups_total, idx_capacity;
     int sel;
-    long long sel_groups, sel_entries;
+    long long sel_entries;
 };
 
-// true iff this launch is the one that was chosen (uniform over the grid)
+// true iff this launch has work to do (uniform over the grid)
 __device__ __forceinline__ bool engine_selected(const EngineArgs& a) {
+    if (!(a.flags & kEngList)) return true;
+    const long long total = a.offsets[a.groups_total];
+    if (total > a.idx_capacity) return false;
     if (a.sel == 0) return true;
-    const bool big = a.offsets[a.sel_groups] >= a.sel_entries;
-    return (a.sel == 2) == big;
+    return (a.sel == 2) == (total >= a.sel_entries);
 }
 
-// 128 query rows per work-group, one instantiation per mode; false: no instantiation for ea.flags
-bool launch_engine_bf16(const EngineArgs& ea, unsigned grid, hipStream_t st);
+// Launchers: the launch's hipError_t, or -1 if there is no instantiation for ea.flags.
+// 128 query rows per work-group, one instantiation per mode
+int launch_engine_bf16(const EngineArgs& ea, unsigned grid, hipStream_t st);
 // 256 query rows (two consecutive blocks) per work-group; needs dense mode or an even step
-bool launch_engine_bf16_pp(const EngineArgs& ea, unsigned grid, hipStream_t st);
+int launch_engine_bf16_pp(const EngineArgs& ea, unsigned grid, hipStream_t st);
 
 __global__ void engine_fp32_kernel(EngineArgs a);
 size_t engine_fp32_lds_bytes(int d, int bq);

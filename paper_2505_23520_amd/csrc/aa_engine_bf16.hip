@@ -444,16 +444,16 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
 }
 
 
-bool launch_engine_bf16(const EngineArgs& ea, unsigned grid, hipStream_t st) {
+int launch_engine_bf16(const EngineArgs& ea, unsigned grid, hipStream_t st) {
     switch (ea.flags) {
 #define AA_ENGINE_CASE(F) \
-    case (F): hipLaunchKernelGGL(engine_bf16_kernel<(F)>, dim3(grid), dim3(256), 0, st, ea); return true;
+    case (F): return (int)launch_kernel(engine_bf16_kernel<(F)>, dim3(grid), dim3(256), 0, st, ea);
     AA_ENGINE_CASE(kEngAnchorRegion | kEngStoreState)                 // stage 1
     AA_ENGINE_CASE(kEngList | kEngLoadState | kEngStoreOut)           // stage 3 from the cached state
     AA_ENGINE_CASE(kEngList | kEngAnchorRegion | kEngStoreOut)        // stage 3 recomputing the anchor region
     AA_ENGINE_CASE(kEngAnchorRegion | kEngDense | kEngStoreOut)       // dense causal attention
 #undef AA_ENGINE_CASE
-    default: return false;
+    default: return -1;
     }
 }
 

@@ -472,16 +472,15 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
     }
 }
 
-bool launch_engine_bf16_pp(const EngineArgs& ea, unsigned grid, hipStream_t st) {
+int launch_engine_bf16_pp(const EngineArgs& ea, unsigned grid, hipStream_t st) {
     switch (ea.flags) {
 #define AA_ENGINE_CASE(F) \
-    case (F): hipLaunchKernelGGL(engine_bf16_pp_kernel<(F)>, dim3(grid), dim3(512), 0, st, ea); return true;
+    case (F): return (int)launch_kernel(engine_bf16_pp_kernel<(F)>, dim3(grid), dim3(512), 0, st, ea);
     AA_ENGINE_CASE(kEngList | kEngLoadState | kEngStoreOut)           // stage 3 from the cached state
     AA_ENGINE_CASE(kEngAnchorRegion | kEngDense | kEngStoreOut)       // dense causal attention
 #undef AA_ENGINE_CASE
     default:                                                          // any other mode: flags read at run time
-        hipLaunchKernelGGL(engine_bf16_pp_kernel<-1>, dim3(grid), dim3(512), 0, st, ea);
-        return true;
+        return (int)launch_kernel(engine_bf16_pp_kernel<-1>, dim3(grid), dim3(512), 0, st, ea);
     }
 }
 

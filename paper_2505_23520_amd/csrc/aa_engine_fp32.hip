@@ -21,6 +21,7 @@ __device__ __forceinline__ void engine_fp32_body(const EngineArgs& a, float* sme
     const int lr = tid >> 1, hh = tid & 1;
     const int BQ = p.bq;
 
+    if (!engine_selected(a)) return;
     const Work wk = decode_work(p, p.nblk_max, blockIdx.x);
     const Seq sq = seq_of(p, wk.b);
     const int row0 = wk.i * BQ;

@@ -65,6 +65,7 @@ __global__ void mask_fp32_kernel(SelectArgs a);
 __global__ void pool_k_kernel(SelectArgs a);
 __global__ void mask_block_kernel(SelectArgs a);
 size_t mask_block_lds_bytes(int N, int d, int bq, int step);
+constexpr size_t kMaskBlockLdsMax = 128 * 1024;   // dynamic LDS limit set for mask_block_kernel
 __global__ void zero_i32_kernel(int* x, long long nelem);
 __global__ void count_kernel(SelectArgs a);
 __global__ void scan_kernel(SelectArgs a);

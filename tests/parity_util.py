@@ -5,12 +5,15 @@ The GPU side goes through the C ABI binding only; the expected values come from
 """
 from __future__ import annotations
 
+import dataclasses
+
 import numpy as np
 import torch
 
 from oracle import anchor_oracle as ao
 
 BAND = 1e-3        # selection may differ only where |xbar - s - theta| <= BAND
+ENGINE = None      # a test fixture may force one of the two bf16 tile engines for every DeviceRun
 
 
 def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
@@ -24,6 +27,8 @@ class DeviceRun:
     """Runs the stage-wise entry points and the fused one on a batch of sequences."""
 
     def __init__(self, api, seqs, cfg, dtype, packed=None, want_acc=True):
+        if ENGINE is not None and cfg.engine == 0:
+            cfg = dataclasses.replace(cfg, engine=ENGINE)
         self.api, self.cfg, self.dtype = api, cfg, dtype
         self.seqs = seqs
         self.lens = [s["q"].shape[1] for s in seqs]

@@ -67,7 +67,8 @@ def test_gqa_32k_theta_sweep(api):
 @pytest.mark.parametrize("signal", ["literal", "logit", "peaked"])
 def test_gqa_128k_sampled(api, signal):
     wl = synth.workloads()["gqa_128k"]
-    samples = [(0, 0, 0), (0, 7, 1), (0, 13, 20), (0, 26, 41), (0, 31, 63)]
+    # groups 1..3 are the first with candidates (less than one key chunk of the mask kernel)
+    samples = [(0, 0, 0), (0, 7, 1), (0, 20, 2), (0, 3, 3), (0, 13, 20), (0, 26, 41), (0, 31, 63)]
     theta = 3.0 * wl.theta if signal == "peaked" else wl.theta     # as bench.py runs it
     run, worst, stats = _run(api, wl, _cfg(api, wl, theta=theta), signal, samples)
     if signal == "peaked":      # the planted columns before a group's window are kept, little else

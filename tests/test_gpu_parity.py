@@ -25,9 +25,10 @@ def api():
 def engine_mode(request, api):
     """Every test runs with the bf16 engine chosen per launch and with each of the two engines forced
     (the 256-row engine falls back to the 128-row one where it does not apply)."""
-    api.anchor_set_engine(request.param)
+    import parity_util
+    parity_util.ENGINE = request.param
     yield request.param
-    api.anchor_set_engine(0)
+    parity_util.ENGINE = None
 
 
 def _wl(name, dtype, lens, Hq, Hkv, d, block, seed, n_planted, mag=(2.5, 2.5), sink=4, q_shift=True, ar1=0.0):
@@ -153,8 +154,9 @@ def test_dense_flash_matches_oracle(api):
 
 
 def test_bf16_recompute_anchor_in_stage3(api):
-    """sparse_attn with M = L = Acc = NULL computes the anchor region itself."""
-    from parity_util import DeviceRun
+    """sparse_attn with M = L = Acc = NULL computes the anchor region itself: O and lse against the
+    oracle (on the lists of the cached-state run, which check_groups verifies as well)."""
+    from parity_util import DeviceRun, check_groups
     wl = _wl("t", "bf16", [2048], 4, 2, 128, 128, 70, 32)
     cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=4.5)
     seqs = [synth.make_sequence(wl, 0, signal="logit")]
@@ -164,8 +166,85 @@ def test_bf16_recompute_anchor_in_stage3(api):
     B = run.buf
     api.sparse_attn(run.p, run.q, run.k, run.v, None, None, None, B["counts"], B["offsets"], B["idx"], out2, lse2)
     torch.cuda.synchronize()
-    assert (out2.float() - run.out.float()).abs().max().item() <= 1e-2
-    assert (lse2 - B["lse"]).abs().max().item() <= 1e-4
+    worst = check_groups(run, _all_samples(run), check_state=False, out=out2, lse=lse2)
+    assert worst["selected"] > 0
+
+
+def _plant_columns(wl, cols, mag):
+    """Input edit: every query gets d^(1/4) u and the key columns `cols` get mag d^(1/4) u along a
+    fixed unit direction u, so that these columns' logits sit about mag above the background's."""
+    def edit(seqs):
+        u = np.random.default_rng(99).standard_normal(wl.d)
+        u /= np.linalg.norm(u)
+        for s in seqs:
+            s["q"] += (wl.d ** 0.25 * u).astype(np.float32)
+            s["k"][:, cols] += (mag * wl.d ** 0.25 * u).astype(np.float32)
+            s["q"], s["k"] = synth.round_to_bf16(s["q"]), synth.round_to_bf16(s["k"])
+    return edit
+
+
+@pytest.mark.parametrize("N,step,theta,long_lists", [(2560, 2, 6.0, False), (2560, 4, 6.0, False),
+                                                     (16384, 2, 4.0, True)])
+def test_bf16_listed_columns_far_above_the_anchor(api, N, step, theta, long_lists):
+    """Rows whose maximum lies outside the anchor region (Sec. 2.2.2): no sink, and in the first half
+    of the sequence planted columns whose logits exceed the anchor of the later rows by more than
+    ten nats; even step.  Stage 3 then has to raise the reference of its exponentials above the
+    cached anchor and rescale the cached state (the m' = max(m, max(qk)) update of Algorithm 3) --
+    in both tile engines, and, with lists of 48 tiles and more per group, in the engine the
+    automatic choice picks for long lists."""
+    from oracle import anchor_oracle as ao
+    from parity_util import DeviceRun, check_groups, oracle_params
+    wl = _wl("t", "bf16", [N], 2, 1, 128, 128, 77, 0, sink=0)
+    cfg = api.Config(block=128, n_init=128, window=128, step=step, theta=theta)
+    seqs = [synth.make_sequence(wl, 0, signal="logit")]
+    _plant_columns(wl, np.arange(130, N // 2 - 64, 53 if N < 8192 else 61), 22.0)(seqs)
+    run = DeviceRun(api, seqs, cfg, "bf16").stages()
+    assert int(run.buf["flag"]) == 0
+    span = 128 * step
+    ng = N // span
+    if long_lists:
+        mean_tiles = int(run.buf["offsets"][-1]) / 64 / run.sizes.groups
+        assert mean_tiles >= 48, mean_tiles          # the automatic choice runs the 256-row engine
+        samples = [(0, 0, 1), (0, 1, ng // 2), (0, 1, ng - 2), (0, 0, ng - 1)]
+    else:
+        samples = _all_samples(run)
+    check_groups(run, samples)
+    # the case is what it claims: in the last group the selected columns lift most rows' maximum
+    # ten nats and more above their anchor
+    q, k, v = seqs[0]["q"][0], seqs[0]["k"][0], seqs[0]["v"][0]
+    ref = ao.run_group(q, k, v, oracle_params(run.cfg, 128), ng - 1)
+    assert ref["M"].max() < 8.0
+    rows_above = int((ref["lse"] - ref["M"] >= 10.0).sum())
+    assert rows_above >= 0.75 * ref["M"].size, rows_above
+
+
+def test_packed_batch_needing_the_whole_idx_capacity(api):
+    """Packed sequences that each reach one row into their last group, theta = +inf: every candidate
+    of every group is selected, which needs exactly the capacity anchor_sizes() promises (a group
+    counts in full once it has one row).  Through the fused entry point, against dense attention."""
+    from parity_util import DeviceRun
+    lens = [1537, 1537, 2047]
+    wl = _wl("t", "bf16", lens, 4, 2, 128, 128, 35, 8)
+    cfg = api.Config(block=128, n_init=128, window=128, step=4, theta=float("inf"))
+    seqs = [synth.make_sequence(wl, s, signal="logit") for s in range(3)]
+    run = DeviceRun(api, seqs, cfg, "bf16", packed=True).stages()
+    assert int(run.buf["flag"]) == 0
+    span = 128 * 4
+    need = 0
+    counts = run.buf["counts"].cpu().numpy()
+    for b, n in enumerate(lens):
+        for h in range(4):
+            for g in range((n + span - 1) // span):
+                cand = max(128, g * span - 128) - 128
+                assert counts[run.grp_index(b, h, g)] == cand
+                need += (cand + 63) // 64 * 64
+    assert need == run.sizes.idx_capacity_max == int(run.buf["offsets"][-1])
+    out, lse, stats = run.fused()
+    assert torch.equal(out, run.out)
+    dense, dlse = run.dense()
+    assert (dense.float() - out.float()).abs().max().item() <= 2e-2
+    assert (dlse - lse).abs().max().item() <= 4e-3
+    assert int(stats[0]) == 4 * sum(n * (n + 1) // 2 for n in lens)
 
 
 @pytest.mark.parametrize("dtype,d,block", [("bf16", 128, 128), ("fp32", 64, 64)])
@@ -260,6 +339,14 @@ def test_overflow_flag_and_capacity(api):
     assert int(B["flag"]) == 1
     assert torch.all(small[1024:] == -7)            # nothing written past the capacity
     assert int(B["offsets"][-1]) == run.sizes.idx_capacity_max   # offsets stay exact
+    # lists that did not fit are incomplete: stage 3 must not read them (nor past the buffer) and
+    # leaves the output alone
+    sentinel = torch.full_like(run.out, 3.0)
+    lse = torch.full_like(B["lse"], -5.0)
+    api.sparse_attn(run.p, run.q, run.k, run.v, B["M"], B["L"], B["Acc"], B["counts"], B["offsets"], small, sentinel,
+                    lse, idx_capacity=1024)
+    torch.cuda.synchronize()
+    assert torch.all(sentinel == 3.0) and torch.all(lse == -5.0)
 
 
 def test_determinism(api):

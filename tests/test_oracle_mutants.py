@@ -33,11 +33,13 @@ MUTANTS = [
     ("pooled score not scaled", "double diff = xbar[b] - c->sigma * s;", "double diff = xbar[b] - s;", 0),
     ("all blocks of a group must agree (AND instead of OR)", "if (diff < mg) mg = diff;", "if (mg == INFINITY || diff > mg) mg = diff;", 0),
     ("threshold added instead of subtracted", "mg -= c->theta;", "mg += c->theta;", 0),
+    ("strict threshold test (< for <=)", "sel[j] = (mg <= 0.0) ? 1 : 0;", "sel[j] = (mg < 0.0) ? 1 : 0;", 0),
     ("selected columns not attended", "if (in_anchor(c, r, j) || sel[j]) {", "if (in_anchor(c, r, j)) {", 0),
     ("output not normalised", "for (int t = 0; t < d; ++t) o[t] /= l;", "for (int t = 0; t < d; ++t) o[t] /= 1.0;", 0),
     ("lse without the maximum", "lse[r - r0] = m + log(l);", "lse[r - r0] = log(l);", 0),
     ("block variant: block mean divided by the wrong count", "kbar[t] /= (double)b_kv;", "kbar[t] /= (double)(b_kv + 1);", 0),
     ("block variant: difference with the wrong sign", "double diff = xbar[b] - c->sigma * s;", "double diff = c->sigma * s - xbar[b];", 1),
+    ("block variant: strict threshold test (< for <=)", "sel[j] = (mg <= 0.0) ? 1 : 0;", "sel[j] = (mg < 0.0) ? 1 : 0;", 1),
     ("block variant: one block too many", "J < W / b_kv; ++J", "J <= W / b_kv - 0 && J < c->N / b_kv; ++J", 0),
 ]
 

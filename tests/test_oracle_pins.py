@@ -144,6 +144,9 @@ def test_hand_worked_example(golden_dir):
         np.testing.assert_array_equal(g["M"], [7.5, 2.5])
         assert g["xbar"][0] == 5.0 and g["qbar"][0, 0] == 2.0
         assert list(g["idx"]) == want
+        # a key block of one column is a stripe: block granularity has the same boundary (<=)
+        gb = ao.run_group(q, k, v, ao.OracleParams(b_q=2, n_init=1, w=2, step=1, theta=theta, sigma=0.5, b_kv=1), 3)
+        assert list(gb["idx"]) == want
         # row 6 attends {0,4,5,6} + selected columns; scores 0.5*3*k
         keys = sorted(set([0, 4, 5, 6]) | set(want))
         e = np.array([math.exp(1.5 * float(k[j, 0])) for j in keys])
