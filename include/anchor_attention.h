@@ -161,6 +161,23 @@ int stripe_select(const aa_params *params, const void *q, const void *k, const f
                   int32_t *overflow_flag, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * stripe_select for callers that cannot allocate device memory or bring a workspace (code
+ * under HIP graph capture, serving loops, harnesses that forbid hipMalloc): same arguments
+ * and results as stripe_select, but its scratch is a device array of
+ * AA_NOALLOC_SCRATCH_BYTES that is part of the library (one copy per GPU, held until the
+ * process ends) and the call allocates nothing.  AA_EWORKSPACE if the parameters need more
+ * than that (aa_sizes.select_ws_bytes; the 128k-token, 32-head, step-16 workload needs
+ * 48 MiB).  All calls on one GPU share the array: calls that overlap in time on one GPU
+ * (different streams or threads) race; calls ordered on one stream do not.  The first call
+ * on a GPU looks the array's address up (hipGetSymbolAddress), so make that call outside a
+ * graph capture.
+ */
+#define AA_NOALLOC_SCRATCH_BYTES (64u << 20)
+int stripe_select_noalloc(const aa_params *params, const void *q, const void *k,
+                          const float *xa_pooled, int32_t *counts, int64_t *offsets, int32_t *idx,
+                          int64_t idx_capacity, int32_t *overflow_flag, void *stream);
+
+/*
  * Stage 3, fine-grained sparse attention (Sec. 3.3, Eq. 3-5; Algorithm 3).
  * Continues the online softmax of every row from (M, L, Acc) over the gathered
  * K/V rows of its group's list, out = acc / l.  If M, L and Acc are all NULL the

@@ -54,6 +54,7 @@ _SIGNATURES = {
     "anchor_workspace_bytes": (ctypes.c_int, [_PP, ctypes.POINTER(ctypes.c_size_t)]),
     "anchor_compute": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, _P, _P]),
     "stripe_select": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, ctypes.c_int64, _P, _P, ctypes.c_size_t, _P]),
+    "stripe_select_noalloc": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, ctypes.c_int64, _P, _P]),
     "sparse_attn": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int64, _P, _P, _P]),
     "anchor_attention_prefill": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, _P]),
     "dense_causal_flash": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P]),
@@ -178,6 +179,13 @@ def stripe_select(p, q, k, xa_pooled, counts, offsets, idx, overflow_flag, ws, s
     _check(_lib.stripe_select(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(xa_pooled), _ptr(counts), _ptr(offsets),
                               _ptr(idx), cap, _ptr(overflow_flag), _ptr(ws),
                               0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def stripe_select_noalloc(p, q, k, xa_pooled, counts, offsets, idx, overflow_flag, stream=None, idx_capacity=None):
+    """stripe_select with the library's own static scratch: no workspace argument, no allocation."""
+    cap = idx.numel() if idx_capacity is None else idx_capacity
+    _check(_lib.stripe_select_noalloc(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(xa_pooled), _ptr(counts),
+                                      _ptr(offsets), _ptr(idx), cap, _ptr(overflow_flag), _stream(stream)))
 
 
 def sparse_attn(p, q, k, v, M, L, Acc, counts, offsets, idx, out, lse=None, stream=None, idx_capacity=None):

@@ -176,6 +176,30 @@ int make_plan(const aa_params* p, Plan* pl) {
 
 bool misaligned(const void* ptr) { return ((uintptr_t)ptr & 15) != 0; }
 
+// ---- workspace of stripe_select_noalloc: a device array that is part of the loaded library, one
+// copy per GPU, held until the process ends.  Its name is a host-side handle, not a device
+// address: host code uses the address hipGetSymbolAddress reports for the current device.
+constexpr size_t kScratchBytes = (size_t)AA_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) static unsigned char scratch[kScratchBytes];
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    AA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return AA_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        AA_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return AA_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return AA_OK;
+}
+
 // kernels that ask for more dynamic LDS than the default limit: raised once per process
 std::once_flag g_attr_once;
 hipError_t g_attr_status = hipSuccess;
@@ -395,6 +419,22 @@ int stripe_select(const aa_params* params, const void* q, const void* k, const f
     if (!q || !k || !xa_pooled || !counts || !offsets || !idx || !overflow_flag || !ws) return AA_EINVAL;
     if (idx_capacity < 0 || misaligned(q) || misaligned(k) || misaligned(idx) || misaligned(ws)) return AA_EINVAL;
     if (ws_bytes < pl.sz.select_ws_bytes) return AA_EWORKSPACE;
+    return run_select(pl, params, q, k, xa_pooled, counts, offsets, idx, idx_capacity, overflow_flag, (char*)ws,
+                      (hipStream_t)stream);
+}
+
+int stripe_select_noalloc(const aa_params* params, const void* q, const void* k, const float* xa_pooled,
+                          int32_t* counts, int64_t* offsets, int32_t* idx, int64_t idx_capacity,
+                          int32_t* overflow_flag, void* stream) {
+    Plan pl;
+    int rc = make_plan(params, &pl);
+    if (rc != AA_OK) return rc;
+    if (!q || !k || !xa_pooled || !counts || !offsets || !idx || !overflow_flag) return AA_EINVAL;
+    if (idx_capacity < 0 || misaligned(q) || misaligned(k) || misaligned(idx)) return AA_EINVAL;
+    if (pl.sz.select_ws_bytes > kScratchBytes) return AA_EWORKSPACE;
+    void* ws = nullptr;
+    rc = scratch_of_current_device(&ws);
+    if (rc != AA_OK) return rc;
     return run_select(pl, params, q, k, xa_pooled, counts, offsets, idx, idx_capacity, overflow_flag, (char*)ws,
                       (hipStream_t)stream);
 }
