@@ -301,10 +301,13 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
         AA_LAUNCH(mask_block_kernel, ggrp, dim3(256), mask_block_lds_bytes(kp.N, kp.d, kp.bq, kp.step), st, sa);
     } else if (p->dtype == AA_BF16) {
         AA_LAUNCH(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
-        // row tiles are folded in pairs (short with long); the longest sequence bounds every other
-        const int ny = (int)cdiv(kp.nblk_max, mask_row_tile(kp.step));
-        const dim3 gm((unsigned)mask_grid_x(kp.nblk_max, kp.step, kp.bq, kp.w, kp.n_init),
-                      (unsigned)((ny + 1) / 2), (unsigned)(kp.B * kp.Hq));
+        // one work-group per (query head, row tile, key chunk with candidates); the longest
+        // sequence bounds every other
+        sa.mask_items = mask_pair_items(kp.nblk_max, kp.step, kp.bq, kp.w, kp.n_init);
+        sa.mask_total = (long long)sa.mask_items * kp.Hq * kp.B;
+        sa.mask_per_xcd = cdiv(sa.mask_total, 8);
+        if (sa.mask_per_xcd * 8 > 0x7fffffffll) return AA_EUNSUPPORTED;
+        const dim3 gm((unsigned)(sa.mask_per_xcd > 0 ? sa.mask_per_xcd * 8 : 8));
         AA_LAUNCH(mask_bf16_kernel, gm, dim3(256), 0, st, sa);
     } else {
         AA_LAUNCH(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);

@@ -23,19 +23,15 @@ __host__ __device__ inline int mask_tile_chunks(int nblk, int rt, int step, int 
     const int span = kMaskChunkKeys * kMaskChunksPerWG;
     return Wmax > key_lo ? (Wmax - key_lo + span - 1) / span : 0;
 }
-// Grid width: row tiles y and ny - 1 - y share one grid row (causal fold: a short and a long tile
-// together have about the same number of chunks everywhere), so nearly every work-group has work.
-__host__ __device__ inline int mask_grid_x(int nblk, int step, int bq, int w, int n_init) {
+// Work items of one (sequence, KV head) pair in the bf16 mask kernel: one per (row tile, key chunk
+// that holds candidates of the tile).  The count for the longest sequence sizes the grid; a
+// shorter sequence has fewer and its surplus work-groups return.
+__host__ __device__ inline int mask_pair_items(int nblk, int step, int bq, int w, int n_init) {
     const int RT = mask_row_tile(step);
     const int ny = (nblk + RT - 1) / RT;
-    int gx = 1;
-    for (int y = 0; 2 * y < ny; ++y) {
-        const int m = ny - 1 - y;
-        const int n = mask_tile_chunks(nblk, y, step, bq, w, n_init) +
-                      (m != y ? mask_tile_chunks(nblk, m, step, bq, w, n_init) : 0);
-        gx = n > gx ? n : gx;
-    }
-    return gx;
+    int n = 0;
+    for (int y = 0; y < ny; ++y) n += mask_tile_chunks(nblk, y, step, bq, w, n_init);
+    return n;
 }
 
 struct SelectArgs {
@@ -56,6 +52,10 @@ struct SelectArgs {
     long long idx_capacity;
     int* overflow;
     long long groups_total;
+    // bf16 mask kernel: work items per (sequence, KV head) pair for the longest sequence, total
+    // work-groups, and work-groups per XCD (see mask_bf16_kernel)
+    int mask_items;
+    long long mask_total, mask_per_xcd;
 };
 
 __global__ void pool_q_bf16_kernel(SelectArgs a);

@@ -84,13 +84,21 @@ __global__ __launch_bounds__(128) void pool_q_fp32_kernel(SelectArgs a) {
 }
 
 // ------------------------------------------------------------------ mask, bf16 MFMA
-// grid (key chunks of a folded pair of row tiles, pairs of row tiles, B*Hq), 256 threads = 4 waves,
-// three work-groups per CU.
-// A row tile holds RT = 128 - 128 % step pooled rows, so no group straddles two tiles; wave w owns
-// its rows 32 w .. 32 w + 31.  The chunk's keys pass through LDS in 64-key tiles (16-byte
+// One work-group = one (query head, row tile, key chunk): 256 threads = 4 waves, three work-groups
+// per CU.  A row tile holds RT = 128 - 128 % step pooled rows, so no group straddles two tiles; wave
+// w owns its rows 32 w .. 32 w + 31.  The chunk's keys pass through LDS in 64-key tiles (16-byte
 // direct-to-LDS loads, two stages, same padded group layout as the attention engine).
 // C[key][row] = K qbar^T: keys are the M dimension, pooled rows the N dimension, so one lane owns
 // one pooled row and collects the compare bits of its row in registers.
+//
+// Grid: one dimension.  Every launched work-group has exactly one chunk of work (row tiles only
+// count the chunks below their last group's window).  A key chunk (256 KB of K) is needed by the
+// query heads of its KV head times the row tiles at or above it -- up to 32 work-groups at 128k
+// tokens -- and is read from HBM once if those run at the same time on one XCD (each XCD has its
+// own L2).  The hardware deals consecutive work-group ids round-robin to the 8 XCDs, so id
+// -> logical index L = (id % 8) * per_xcd + id / 8 gives each XCD a contiguous range of L, walked
+// in order; L enumerates (sequence, KV head) pairs, inside a pair the key chunks in ascending
+// order, inside a chunk the row tiles that need it, and the query heads of the KV head fastest.
 constexpr int kMaskTileKeys = 64;
 constexpr int kMaskChunkTiles = kMaskChunkKeys / kMaskTileKeys;   // tiles per work-group
 constexpr int kKGrp = 1024 + 16;                         // bytes per group of four K rows + pad
@@ -110,21 +118,34 @@ __device__ __forceinline__ void lds_barrier() {
 
 __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
     const KParams& p = a.p;
-    const int b = blockIdx.z / p.Hq, h = blockIdx.z % p.Hq, hk = h / p.grp;
+    const long long L = (long long)(blockIdx.x & 7u) * a.mask_per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= a.mask_per_xcd || L >= a.mask_total) return;
+    const int per_pair = a.mask_items * p.grp;
+    const int pr = (int)(L / per_pair), e = (int)(L % per_pair);
+    const int b = pr / p.Hkv, hk = pr % p.Hkv, h = hk * p.grp + e % p.grp;
     const Seq sq = seq_of(p, b);
     const int nblk = (sq.len + p.bq - 1) / p.bq;
     const int RT = mask_row_tile(p.step);
-    // Grid row y serves row tile y with its first work-groups and row tile ny - 1 - y, chunks counted
-    // from the grid row's far end, with the rest.
     const int ny = (nblk + RT - 1) / RT;
-    int rt = blockIdx.y, chunk = blockIdx.x;
-    if (2 * rt >= ny) return;
-    if (chunk >= mask_tile_chunks(nblk, rt, p.step, p.bq, p.w, p.n_init)) {
-        const int m = ny - 1 - rt;
-        chunk = (int)gridDim.x - 1 - (int)blockIdx.x;
-        if (m == rt || chunk >= mask_tile_chunks(nblk, m, p.step, p.bq, p.w, p.n_init)) return;
-        rt = m;
+    // item e / grp of this sequence -> (chunk, row tile).  Row tile y has candidates in its first
+    // n(y) chunks and n is non-decreasing in y, so chunks n(y-1) .. n(y)-1 are needed by the
+    // ny - y row tiles y .. ny-1: walk these levels.
+    int rt = -1, chunk = 0;
+    {
+        int item = e / p.grp, prev = 0;
+        for (int y = 0; y < ny; ++y) {
+            const int n = mask_tile_chunks(nblk, y, p.step, p.bq, p.w, p.n_init);
+            const int width = ny - y, items = (n - prev) * width;
+            if (item < items) {
+                chunk = prev + item / width;
+                rt = y + item % width;
+                break;
+            }
+            item -= items;
+            prev = n;
+        }
     }
+    if (rt < 0) return;                                  // a shorter sequence of a packed batch
     const int row_t0 = rt * RT;                          // first pooled row (query block) of the tile
     if (row_t0 >= nblk) return;
     const int rows_here = min(RT, nblk - row_t0);
