@@ -42,7 +42,7 @@ struct Plan {
     aa_sizes sz;
     int nwords;
     // byte offsets inside the workspaces
-    size_t sel_qhi, sel_qlo, sel_bits, sel_segc, sel_kp;               // stripe_select workspace
+    size_t sel_qhi, sel_qlo, sel_qln, sel_kmax, sel_bits, sel_segc, sel_kp;   // stripe_select workspace
     size_t pf_M, pf_L, pf_Acc, pf_xa, pf_counts, pf_offsets, pf_flag, pf_idx, pf_sel;  // prefill workspace
 };
 
@@ -112,7 +112,7 @@ int make_plan(const aa_params* p, Plan* pl) {
     k.nblk_max = (int)cdiv(p->N, p->block_q);
     k.ngrp_max = (int)cdiv(p->N, span);
     // launch grids put heads (times sequences) on y / z, and the fp32 mask kernel puts groups on y
-    if ((long long)p->Hq * p->B > 65535) return AA_EUNSUPPORTED;
+    if ((long long)p->Hq * p->B > 65535 || p->Hq + p->Hkv > 65535) return AA_EUNSUPPORTED;
     if (p->dtype == AA_FP32 && k.ngrp_max > 65535) return AA_EUNSUPPORTED;
 
     aa_sizes& s = pl->sz;
@@ -150,9 +150,11 @@ int make_plan(const aa_params* p, Plan* pl) {
     if (p->dtype == AA_BF16) {
         pl->sel_qhi = off; off += align256((size_t)s.blocks * 128 * 2);
         pl->sel_qlo = off; off += align256((size_t)s.blocks * 128 * 2);
+        pl->sel_qln = off; off += align256((size_t)s.blocks * 4);
+        pl->sel_kmax = off; off += align256((size_t)(s.blocks / k.grp) * 4);
     } else {
         pl->sel_qhi = off; off += align256((size_t)s.blocks * p->d * 4);
-        pl->sel_qlo = off;
+        pl->sel_qlo = off; pl->sel_qln = off; pl->sel_kmax = off;
     }
     pl->sel_bits = off; off += align256((size_t)s.groups * pl->nwords * 4);
     pl->sel_segc = off; off += align256((size_t)s.groups * cdiv(pl->nwords, 64) * 4);
@@ -279,6 +281,8 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     sa.qp_hi = ws + pl.sel_qhi; sa.qp_lo = ws + pl.sel_qlo; sa.qp_f32 = (float*)(ws + pl.sel_qhi);
     sa.bits = (unsigned*)(ws + pl.sel_bits);
     sa.kp_f32 = (float*)(ws + pl.sel_kp);
+    sa.qlo_norm = (float*)(ws + pl.sel_qln);
+    sa.kmax_blk = nullptr;
     sa.segcount = (int*)(ws + pl.sel_segc);
     sa.nseg = (int)cdiv(pl.nwords, 64);
     sa.is_bf16 = p->dtype == AA_BF16;
@@ -300,7 +304,8 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
         AA_LAUNCH(pool_k_kernel, dim3(kp.nblk_max, kp.Hkv, kp.B), dim3(256), 0, st, sa);
         AA_LAUNCH(mask_block_kernel, ggrp, dim3(256), mask_block_lds_bytes(kp.N, kp.d, kp.bq, kp.step), st, sa);
     } else if (p->dtype == AA_BF16) {
-        AA_LAUNCH(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
+        sa.kmax_blk = (float*)(ws + pl.sel_kmax);
+        AA_LAUNCH(pool_q_bf16_kernel, dim3(kp.nblk_max, kp.Hq + kp.Hkv, kp.B), dim3(256), 0, st, sa);
         // one work-group per (query head, row tile, key chunk with candidates); the longest
         // sequence bounds every other
         sa.mask_items = mask_pair_items(kp.nblk_max, kp.step, kp.bq, kp.w, kp.n_init);

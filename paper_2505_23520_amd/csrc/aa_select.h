@@ -41,6 +41,8 @@ struct SelectArgs {
     void *qp_hi, *qp_lo;      // bf16 path: pooled queries, hi / lo parts, rows of 128
     float* qp_f32;            // fp32 path: pooled queries, rows of d
     float* kp_f32;            // block granularity: pooled keys per (KV head, key block), rows of d
+    float* qlo_norm;          // bf16 path: Euclidean norm of the lo part of each pooled query row
+    float* kmax_blk;          // bf16 stripe path: largest key norm per (KV head, key block)
     int is_bf16;              // element type of q, k
     unsigned* bits;           // [groups][nwords] selection bit words, bit (j % 32) of word j / 32
     int nwords;               // ceil(N / 32)

@@ -29,16 +29,50 @@ __device__ __forceinline__ unsigned short f_to_bf16_rne(float f) {
 }  // namespace
 
 // ------------------------------------------------------------------ pool_q
-// grid (nblk_max, Hq, B).  bf16: 256 threads, thread (c, rs) sums the 16-byte chunk c of rows
-// rs, rs + 16, ...; writes hi/lo bf16 rows of 128.  fp32: 128 threads, float rows of d.
+// grid (nblk_max, Hq [+ Hkv], B).  bf16: 256 threads, thread (c, rs) sums the 16-byte chunk c of rows
+// rs, rs + 16, ...; writes hi/lo bf16 rows of 128 and the norm of the lo row.  With kmax_blk set the
+// grid has Hkv more rows in y: those work-groups write the largest key norm of their key block
+// (the mask kernel bounds |<lo, k>| by |lo| |k| to decide whether the lo products are needed).
+// fp32: 128 threads, float rows of d.
 __global__ __launch_bounds__(256) void pool_q_bf16_kernel(SelectArgs a) {
     const KParams& p = a.p;
-    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int i = blockIdx.x, b = blockIdx.z;
     const Seq sq = seq_of(p, b);
     const int r0 = i * p.bq;
     if (r0 >= sq.len) return;
     const int r1 = min(r0 + p.bq, sq.len);
     const int tid = threadIdx.x, c = tid & 15, rs = tid >> 4;
+    __shared__ float red[16][128];
+    if ((int)blockIdx.y >= p.Hq) {
+        // key block i of KV head hk: squared norm of every row (16 threads per row), largest
+        const int hk = blockIdx.y - p.Hq;
+        const unsigned short* src = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, b, hk, 0) + 8 * c;
+        float big = 0.f;
+        for (int r = r0 + rs; r < r1; r += 16) {
+            const uintx4 x = *(const uintx4*)(src + (long long)r * p.ks[2]);
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = __uint_as_float(x[e] << 16), hi = __uint_as_float(x[e] & 0xffff0000u);
+                ss = fmaf(lo, lo, ss);
+                ss = fmaf(hi, hi, ss);
+            }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+            big = fmaxf(big, ss);
+        }
+#pragma unroll
+        for (int off = 32; off >= 16; off >>= 1) big = fmaxf(big, __shfl_xor(big, off, 64));
+        if ((tid & 63) == 0) red[0][tid >> 6] = big;
+        __syncthreads();
+        if (tid == 0) {
+            const long long kb = (p.packed ? (long long)hk * p.blk_cap + sq.blk0
+                                           : ((long long)b * p.Hkv + hk) * p.blk_cap) + i;
+            a.kmax_blk[kb] = sqrtf(fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3])));
+        }
+        return;
+    }
+    const int h = blockIdx.y;
     const unsigned short* src = (const unsigned short*)a.q + tok_offset(p, p.qs, sq, b, h, 0) + 8 * c;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int r = r0 + rs; r < r1; r += 16) {
@@ -49,7 +83,6 @@ __global__ __launch_bounds__(256) void pool_q_bf16_kernel(SelectArgs a) {
             acc[2 * e + 1] += __uint_as_float(x[e] & 0xffff0000u);
         }
     }
-    __shared__ float red[16][128];
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[rs][8 * c + e] = acc[e];
     __syncthreads();
@@ -64,6 +97,12 @@ __global__ __launch_bounds__(256) void pool_q_bf16_kernel(SelectArgs a) {
         const long long bi = blk_index(p, sq, b, h, i);
         ((unsigned*)a.qp_hi)[bi * 64 + tid] = (unsigned)h0 | ((unsigned)h1 << 16);
         ((unsigned*)a.qp_lo)[bi * 64 + tid] = (unsigned)l0 | ((unsigned)l1 << 16);
+        // what the hi + lo pair leaves out (below 2^-16 of the entry) is far inside the tolerance of
+        // the decision; the norm of lo bounds what leaving out lo would change
+        float ln = bf16_to_f(l0) * bf16_to_f(l0) + bf16_to_f(l1) * bf16_to_f(l1);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) ln += __shfl_xor(ln, off, 64);
+        if (tid == 0) a.qlo_norm[bi] = sqrtf(ln);
     }
 }
 
@@ -184,6 +223,7 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
     }
     // theta minus the pooled anchor of the lane's row; -inf = no such row (never selects)
     const float toff = rok ? p.theta - (p.use_anchor ? a.xa[bi] : 0.f) : -INFINITY;
+    const float lo_norm = rok ? a.qlo_norm[bi] : 0.f;
 
     const unsigned short* kbase = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, b, hk, 0);
     const unsigned kstb = (unsigned)p.ks[2] * 2u;
@@ -211,6 +251,15 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
     if (chunk0 >= Wmax) break;
     const int chunk1 = min(chunk0 + kMaskChunkKeys, ((Wmax + kMaskTileKeys - 1) / kMaskTileKeys) * kMaskTileKeys);
     const int ntiles = (chunk1 - chunk0) / kMaskTileKeys;
+    // |sigma <lo, k>| <= sigma |lo| max|k| over the chunk's keys: a score whose margin from the hi
+    // products alone is farther from zero than that keeps its sign whatever the lo products add
+    float kbig = 0.f;
+    {
+        const long long kb0 = p.packed ? (long long)hk * p.blk_cap + sq.blk0 : ((long long)b * p.Hkv + hk) * p.blk_cap;
+        const int J1 = min(chunk1 - 1, sq.len - 1) / p.bq;
+        for (int J = chunk0 / p.bq; J <= J1; ++J) kbig = fmaxf(kbig, a.kmax_blk[kb0 + J]);
+    }
+    const float lo_bound = 1.001f * p.sigma * lo_norm * kbig;
     // After the tile loop: OR the rows of each group, clip to the group's candidate range, write the
     // bit words of the chunk.  (This stays outside the tile loop: before an inner loop that reads
     // LDS, and before an LDS atomic, the compiler waits for every outstanding asynchronous load
@@ -256,35 +305,61 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
         __builtin_amdgcn_s_setprio(2);
         const char* Kb = Kcur + koff;
         floatx16 c[2];
-        // the two accumulators alternate, so no MFMA waits for the one issued just before it
+        // hi products first.  The two accumulators alternate, so no MFMA waits for the one issued
+        // just before it
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const bf16x8 kf0 = *(const bf16x8*)(Kb + 32 * ks);
             const bf16x8 kf1 = *(const bf16x8*)(Kb + 512 + 32 * ks);
-            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, blo[ks], ks == 0 ? kZero16 : c[0], 0, 0, 0);
-            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, blo[ks], ks == 0 ? kZero16 : c[1], 0, 0, 0);
-            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, bhi[ks], c[0], 0, 0, 0);
-            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, bhi[ks], c[1], 0, 0, 0);
+            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, bhi[ks], ks == 0 ? kZero16 : c[0], 0, 0, 0);
+            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, bhi[ks], ks == 0 ? kZero16 : c[1], 0, 0, 0);
         }
         // operand reads run ahead of their MFMAs
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
         for (int i = 0; i < 6; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
         __builtin_amdgcn_s_setprio(0);
-        // Threshold test xbar - sigma s <= theta as the sign of sigma s + (theta - xbar): two
-        // instructions per score (fma, then the sign bit is shifted into a word), no compare / select
-        // chains.  The lane gathers the bits of its 16 keys per 32-key block (accumulator register v
-        // holds key 8 (v / 4) + 4 hf + v % 4), the other half of the wave holds the remaining 16.
+        // Threshold test xbar - sigma s <= theta as the sign of sigma s + (theta - xbar).
+        float mg[2][16];
+        float nearest = INFINITY;                    // smallest |margin| of the lane's 32 scores
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                mg[kb][v] = fmaf(p.sigma, c[kb][v], toff);
+                mg[kb][v + 1] = fmaf(p.sigma, c[kb][v + 1], toff);
+                nearest = fminf(fminf(nearest, fabsf(mg[kb][v])), fabsf(mg[kb][v + 1]));     // v_min3_f32
+            }
+        if (__any(nearest <= lo_bound)) {
+            // some decision of this wave's tile hangs on the lo products: add them (rare: only
+            // margins within ~1e-2 of zero get here)
+            __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 kf0 = *(const bf16x8*)(Kb + 32 * ks);
+                const bf16x8 kf1 = *(const bf16x8*)(Kb + 512 + 32 * ks);
+                c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, blo[ks], c[0], 0, 0, 0);
+                c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, blo[ks], c[1], 0, 0, 0);
+            }
+            __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mg[kb][v] = fmaf(p.sigma, c[kb][v], toff);
+        }
+        // Sign bits shifted into a word (one instruction per score, no compare / select chains).
+        // The lane gathers the bits of its 16 keys per 32-key block (accumulator register v holds
+        // key 8 (v / 4) + 4 hf + v % 4), the other half of the wave holds the remaining 16.
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             unsigned neg = 0;                        // bit v = sign of score v's margin
 #pragma unroll
             for (int v = 15; v >= 0; --v)
-                neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(fmaf(p.sigma, c[kb][v], toff)), 31);
+                neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(mg[kb][v]), 31);
             const unsigned sel = ~neg & 0xffffu;
             unsigned wd = (sel & 0xfu) | ((sel & 0xf0u) << 4) | ((sel & 0xf00u) << 8) | ((sel & 0xf000u) << 12);
             wd <<= 4 * hf;
