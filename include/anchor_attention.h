@@ -38,9 +38,17 @@
  *  ignored, r is replaced by cu_seqlens[b] + r, N is the longest sequence and
  *  total_tokens = cu_seqlens[B].
  *
- *  Per-row arrays (M, L, lse; Acc has d floats per row), float:
+ *  Per-row arrays (M, L, lse), float:
  *      fixed length: row (b,h,r) at (b*Hq + h)*N + r
  *      packed      : row (b,h,r) at h*total_tokens + cu_seqlens[b] + r
+ *  Acc (float, aa_sizes.acc_elems entries):
+ *      AA_FP32: d floats per row, rows indexed as above.
+ *      AA_BF16 (d = 128, b_q = 128): one slab of 128*128 floats per query block, slab index as
+ *      for the per-block arrays below; a slab holds four tiles of 32 rows, tile w = rows
+ *      32w..32w+31 of the block, and inside tile w element (row n, column c) sits at float
+ *          w*4096 + ((c/32)*4 + (c%32)/8)*256 + (n + 32*((c%8)/4))*4 + c%4
+ *      (the register order of the matrix-core accumulators: stage 1 stores and stage 3
+ *      reloads a tile with whole 1 KB bursts).  Rows past the end of a sequence are padding.
  *  Per-block arrays (xa_pooled), float, nblk(b) = ceil(len_b / b_q):
  *      fixed length: (b*Hq + h)*nblk + i
  *      packed      : h*blk_cap + (sum_{b'<b} nblk(b')) + i,  blk_cap from anchor_sizes()
@@ -107,7 +115,7 @@ typedef struct aa_params {
 /* Element counts of every buffer a caller has to provide (host-side arithmetic only). */
 typedef struct aa_sizes {
     int64_t rows;             /* floats in M, L, lse                                            */
-    int64_t acc_elems;        /* floats in Acc (= rows * d)                                     */
+    int64_t acc_elems;        /* floats in Acc (fp32: rows * d; bf16: blocks * b_q * d)         */
     int64_t blk_cap;          /* per-head stride of per-block arrays                            */
     int64_t blocks;           /* floats in xa_pooled (= Hq * blk_cap, times B when fixed length)*/
     int64_t grp_cap;          /* per-head stride of per-group arrays                            */

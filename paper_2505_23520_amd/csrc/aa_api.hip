@@ -141,7 +141,8 @@ int make_plan(const aa_params* p, Plan* pl) {
         s.idx_capacity_max = (int64_t)p->B * p->Hq * padded_candidates(p, k.ngrp_max);
     }
     if (s.idx_capacity_max < kIdxPad) s.idx_capacity_max = kIdxPad;
-    s.acc_elems = s.rows * p->d;
+    // fp32: row-major, d floats per row; bf16: per query block, four 32-row tiles in fragment order
+    s.acc_elems = p->dtype == AA_BF16 ? s.blocks * (int64_t)p->block_q * p->d : s.rows * p->d;
     k.blk_cap = s.blk_cap;
     k.grp_cap = s.grp_cap;
     pl->nwords = (int)cdiv(p->N, 32);

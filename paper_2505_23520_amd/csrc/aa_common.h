@@ -70,6 +70,14 @@ __device__ __forceinline__ long long blk_index(const KParams& p, const Seq& s, i
 __device__ __forceinline__ long long grp_index(const KParams& p, const Seq& s, int b, int h, int g) {
     return p.packed ? (long long)h * p.grp_cap + s.grp0 + g : ((long long)b * p.Hq + h) * p.grp_cap + g;
 }
+// bf16 path (d = 128, b_q = 128): the cached accumulator Acc is kept per query block as four tiles
+// of 32 rows x 128 columns, each tile in the register order of the MFMA accumulators, so that a
+// wave stores and reloads its 64 accumulator registers with 1 KB of consecutive addresses per
+// instruction.  Float offset of tile `tile` of block i; inside the tile, element (row n, column c)
+// sits at ((c / 32) * 4 + (c % 32) / 8) * 256 + (n + 32 * ((c % 8) / 4)) * 4 + c % 4.
+__device__ __forceinline__ long long acc_tile(const KParams& p, const Seq& s, int b, int h, int i, int tile) {
+    return (blk_index(p, s, b, h, i) * 4 + tile) * 4096;
+}
 // Element offset of token r of head h (d contiguous); batch stride unused when packed.
 __device__ __forceinline__ long long tok_offset(const KParams& p, const long long* st, const Seq& s,
                                                 int b, int h, int r) {

@@ -208,12 +208,13 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         mref = a.Min[ri] / p.sigma;
         mtrue = mref;
         l = hf == 0 ? a.Lin[ri] : 0.f;
-        const float* acc = a.Accin + ri * D;
+        // cached accumulator of this wave's 32 rows, stored in fragment order (see acc_tile)
+        const float* acc = a.Accin + acc_tile(p, sq, wk.b, wk.h, wk.i, wave);
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
-                const floatx4 x = *(const floatx4*)(acc + 32 * db + 8 * v4 + 4 * hf);
+                const floatx4 x = *(const floatx4*)(acc + (4 * db + v4) * 256 + 4 * lane);
                 o[db][4 * v4 + 0] = x.x; o[db][4 * v4 + 1] = x.y;
                 o[db][4 * v4 + 2] = x.z; o[db][4 * v4 + 3] = x.w;
             }
@@ -383,28 +384,16 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         const float ms = mtrue * p.sigma;
         if (rok && hf == 0) { a.Mout[ri] = ms; a.Lout[ri] = lt * down; }
         if (a.Accout && wave_rows > 0) {
-            // 16 rows at a time: fragment layout -> row-major in LDS (pitch 132 floats), then 1 KB
-            // contiguous per store instruction (the wave's rows are contiguous in Acc)
-            float* sf = (float*)stg;
-            float* acc = a.Accout + row_index(p, sq, wk.b, wk.h, rw) * D;
+            // fragment order: every store instruction writes 1 KB of consecutive addresses, and stage 3
+            // reads the tile back the same way (no staging through LDS on either side)
+            float* acc = a.Accout + acc_tile(p, sq, wk.b, wk.h, wk.i, wave);
 #pragma unroll
-            for (int ph = 0; ph < 2; ++ph) {
-                if ((n >> 4) == ph) {
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int v4 = 0; v4 < 4; ++v4)
-                            *(floatx4*)(sf + (n & 15) * 132 + 32 * db + 8 * v4 + 4 * hf) =
-                                floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
-                                        o[db][4 * v4 + 3] * down};
-                }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int f4 = 64 * i + lane, row = f4 >> 5, c4 = f4 & 31;
-                    const floatx4 x = *(const floatx4*)(sf + row * 132 + 4 * c4);
-                    if (16 * ph + row < wave_rows) *(floatx4*)(acc + (16 * ph + row) * D + 4 * c4) = x;
-                }
-            }
+                for (int v4 = 0; v4 < 4; ++v4)
+                    *(floatx4*)(acc + (4 * db + v4) * 256 + 4 * lane) =
+                        floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
+                                o[db][4 * v4 + 3] * down};
         }
         if (a.xa) {
             // pooled anchor of the block: mean of M over its rows (Algorithm 2, avgpool of the anchor)

@@ -199,12 +199,14 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
         mref = a.Min[ri] / p.sigma;
         mtrue = mref;
         l = hf == 0 ? a.Lin[ri] : 0.f;
-        const float* acc = a.Accin + ri * D;
+        // cached accumulator of this wave's 32 rows, stored in fragment order (see acc_tile)
+        // (a wave whose rows lie past the end of the sequence reads the pair's first block: in bounds, unused)
+        const float* acc = a.Accin + acc_tile(p, sq, wk.b, wk.h, 2 * wk.i + (wave_on ? chunk >> 2 : 0), chunk & 3);
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
-                const floatx4 x = *(const floatx4*)(acc + 32 * db + 8 * v4 + 4 * hf);
+                const floatx4 x = *(const floatx4*)(acc + (4 * db + v4) * 256 + 4 * lane);
                 o[db][4 * v4 + 0] = x.x; o[db][4 * v4 + 1] = x.y;
                 o[db][4 * v4 + 2] = x.z; o[db][4 * v4 + 3] = x.w;
             }
@@ -430,13 +432,13 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
         const float down = (mref == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mtrue) * c2);
         const float ms = mtrue * p.sigma;
         if (rok && hf == 0) { a.Mout[ri] = ms; a.Lout[ri] = lt * down; }
-        if (rok && a.Accout) {
-            float* acc = a.Accout + ri * D;
+        if (wave_on && a.Accout) {
+            float* acc = a.Accout + acc_tile(p, sq, wk.b, wk.h, 2 * wk.i + (chunk >> 2), chunk & 3);
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int v4 = 0; v4 < 4; ++v4)
-                    *(floatx4*)(acc + 32 * db + 8 * v4 + 4 * hf) =
+                    *(floatx4*)(acc + (4 * db + v4) * 256 + 4 * lane) =
                         floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
                                 o[db][4 * v4 + 3] * down};
         }

@@ -81,6 +81,19 @@ class DeviceRun:
             return out[h, o + r0:o + r1]
         return out[b, h, r0:r1]
 
+    def acc_rows(self, b, h, g, nrows):
+        """Acc of group g's rows as float64 [nrows, d], from the layout include/anchor_attention.h documents."""
+        d, A = self.d, self.buf["Acc"]
+        if self.dtype != "bf16":
+            ri0 = self.row_index(b, h, g * self.cfg.block * self.cfg.step)
+            return A[ri0 * d:(ri0 + nrows) * d].cpu().numpy().astype(np.float64).reshape(-1, d)
+        nb = (nrows + 127) // 128
+        bi0 = self.blk_index(b, h, g * self.cfg.step)
+        slabs = A[bi0 * 16384:(bi0 + nb) * 16384].cpu().numpy().astype(np.float64)
+        # [block, tile w, column block c/32, (c%32)/8, (c%8)/4, row n, c%4] -> [block, w, n, columns]
+        t = slabs.reshape(nb, 4, 4, 4, 2, 32, 4).transpose(0, 1, 5, 2, 3, 4, 6)
+        return t.reshape(nb * 128, 128)[:nrows]
+
     # ---- GPU calls
     def stages(self):
         api, p, B = self.api, self.p, self.buf
@@ -149,7 +162,7 @@ def check_groups(run: DeviceRun, samples, check_state=True, out=None, lse=None):
             worst["M"] = max(worst["M"], np.abs(Mg - ref["M"]).max())
             worst["L"] = max(worst["L"], (np.abs(Lg - ref["L"]) / ref["L"]).max())
             if run.buf["Acc"] is not None:
-                Ag = run.buf["Acc"][ri0 * d:(ri0 + r1 - r0) * d].cpu().numpy().astype(np.float64).reshape(-1, d)
+                Ag = run.acc_rows(b, h, g, r1 - r0)
                 worst["accn"] = max(worst["accn"], np.abs(Ag / Lg[:, None] - ref["Acc"] / ref["L"][:, None]).max())
             nb = ref["xbar"].size
             bi0 = run.blk_index(b, h, g * cfg.step)
