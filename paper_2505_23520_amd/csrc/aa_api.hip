@@ -261,19 +261,25 @@ int launch_engine(const Plan& pl, const aa_params* prm, EngineArgs& ea, hipStrea
     return AA_OK;
 }
 
+// sel_ws (nullable): a stripe_select workspace; the bf16 engines then also leave the pooled queries of
+// stage 2 there (run_select is told so)
 int run_anchor(const Plan& pl, const aa_params* p, const void* q, const void* k, const void* v, float* M, float* L,
-               float* Acc, float* xa, hipStream_t st) {
+               float* Acc, float* xa, char* sel_ws, hipStream_t st) {
     EngineArgs ea;
     memset(&ea, 0, sizeof(ea));
     ea.p = pl.kp;
     ea.flags = kEngAnchorRegion | kEngStoreState;
     ea.q = q; ea.k = k; ea.v = v;
     ea.Mout = M; ea.Lout = L; ea.Accout = Acc; ea.xa = xa;
+    if (sel_ws && p->dtype == AA_BF16) {
+        ea.qp_hi = sel_ws + pl.sel_qhi; ea.qp_lo = sel_ws + pl.sel_qlo; ea.qlo_norm = (float*)(sel_ws + pl.sel_qln);
+    }
     return launch_engine(pl, p, ea, st);
 }
 
+// q_pooled: stage 1 has written the pooled queries into ws already (bf16 only)
 int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k, const float* xa, int32_t* counts,
-               int64_t* offsets, int32_t* idx, int64_t cap, int32_t* flag, char* ws, hipStream_t st) {
+               int64_t* offsets, int32_t* idx, int64_t cap, int32_t* flag, char* ws, bool q_pooled, hipStream_t st) {
     const KParams& kp = pl.kp;
     SelectArgs sa;
     memset(&sa, 0, sizeof(sa));
@@ -297,16 +303,18 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     if (kp.packed)
         AA_LAUNCH(zero_i32_kernel, dim3((unsigned)cdiv(pl.sz.groups, 256)), dim3(256), 0, st, counts,
                   (long long)pl.sz.groups);
+    q_pooled = q_pooled && p->dtype == AA_BF16;
+    sa.pool_skip_q = q_pooled;
     if (p->granularity == AA_BLOCK) {
-        if (p->dtype == AA_BF16)
-            AA_LAUNCH(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
-        else
+        if (p->dtype != AA_BF16)
             AA_LAUNCH(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);
+        else if (!q_pooled)
+            AA_LAUNCH(pool_q_bf16_kernel, gblk, dim3(256), 0, st, sa);
         AA_LAUNCH(pool_k_kernel, dim3(kp.nblk_max, kp.Hkv, kp.B), dim3(256), 0, st, sa);
         AA_LAUNCH(mask_block_kernel, ggrp, dim3(256), mask_block_lds_bytes(kp.N, kp.d, kp.bq, kp.step), st, sa);
     } else if (p->dtype == AA_BF16) {
         sa.kmax_blk = (float*)(ws + pl.sel_kmax);
-        AA_LAUNCH(pool_q_bf16_kernel, dim3(kp.nblk_max, kp.Hq + kp.Hkv, kp.B), dim3(256), 0, st, sa);
+        AA_LAUNCH(pool_q_bf16_kernel, dim3(kp.nblk_max, (q_pooled ? 0 : kp.Hq) + kp.Hkv, kp.B), dim3(256), 0, st, sa);
         // one work-group per (query head, row tile, key chunk with candidates); the longest
         // sequence bounds every other
         sa.mask_items = mask_pair_items(kp.nblk_max, kp.step, kp.bq, kp.w, kp.n_init);
@@ -416,7 +424,7 @@ int anchor_compute(const aa_params* params, const void* q, const void* k, const 
     if (rc != AA_OK) return rc;
     if (!q || !k || !v || !M || !L || !xa_pooled) return AA_EINVAL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(Acc)) return AA_EINVAL;
-    return run_anchor(pl, params, q, k, v, M, L, Acc, xa_pooled, (hipStream_t)stream);
+    return run_anchor(pl, params, q, k, v, M, L, Acc, xa_pooled, nullptr, (hipStream_t)stream);
 }
 
 int stripe_select(const aa_params* params, const void* q, const void* k, const float* xa_pooled, int32_t* counts,
@@ -429,7 +437,7 @@ int stripe_select(const aa_params* params, const void* q, const void* k, const f
     if (idx_capacity < 0 || misaligned(q) || misaligned(k) || misaligned(idx) || misaligned(ws)) return AA_EINVAL;
     if (ws_bytes < pl.sz.select_ws_bytes) return AA_EWORKSPACE;
     return run_select(pl, params, q, k, xa_pooled, counts, offsets, idx, idx_capacity, overflow_flag, (char*)ws,
-                      (hipStream_t)stream);
+                      false, (hipStream_t)stream);
 }
 
 int stripe_select_noalloc(const aa_params* params, const void* q, const void* k, const float* xa_pooled,
@@ -445,7 +453,7 @@ int stripe_select_noalloc(const aa_params* params, const void* q, const void* k,
     rc = scratch_of_current_device(&ws);
     if (rc != AA_OK) return rc;
     return run_select(pl, params, q, k, xa_pooled, counts, offsets, idx, idx_capacity, overflow_flag, (char*)ws,
-                      (hipStream_t)stream);
+                      false, (hipStream_t)stream);
 }
 
 int sparse_attn(const aa_params* params, const void* q, const void* k, const void* v, const float* M, const float* L,
@@ -481,9 +489,11 @@ int anchor_attention_prefill(const aa_params* params, const void* q, const void*
     int64_t* offsets = (int64_t*)(w + pl.pf_offsets);
     int32_t* flag = (int32_t*)(w + pl.pf_flag);
     int32_t* idx = (int32_t*)(w + pl.pf_idx);
-    rc = run_anchor(pl, params, q, k, v, M, L, Acc, xa, st);
+    // the block means of Q (first step of stage 2) come out of stage 1, which holds the block's
+    // queries in registers; the stage-wise entry points compute the same bits in a kernel of their own
+    rc = run_anchor(pl, params, q, k, v, M, L, Acc, xa, w + pl.pf_sel, st);
     if (rc != AA_OK) return rc;
-    rc = run_select(pl, params, q, k, xa, counts, offsets, idx, pl.sz.idx_capacity_max, flag, w + pl.pf_sel, st);
+    rc = run_select(pl, params, q, k, xa, counts, offsets, idx, pl.sz.idx_capacity_max, flag, w + pl.pf_sel, true, st);
     if (rc != AA_OK) return rc;
     rc = run_sparse(pl, params, q, k, v, M, L, Acc, counts, offsets, idx, pl.sz.idx_capacity_max, out, lse, st);
     if (rc != AA_OK) return rc;

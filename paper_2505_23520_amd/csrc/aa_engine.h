@@ -22,6 +22,10 @@ struct EngineArgs {
     const long long* offsets;
     const int* idx;
     float *Mout, *Lout, *Accout, *xa;
+    // stage 1 only, nullable: pooled queries of stage 2 (bf16 hi / lo rows of 128, norm of lo),
+    // written from the Q fragments the block's work-group holds anyway (see aa_pool.h)
+    void *qp_hi, *qp_lo;
+    float* qlo_norm;
     void* out;
     float* lse;
     // List-driven calls: offsets[groups_total] is the total (padded) list length.  Lists that do not

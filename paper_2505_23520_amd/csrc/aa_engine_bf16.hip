@@ -26,6 +26,7 @@
 // anchor that stage 1 exports, is tracked separately.
 #include "aa_common.h"
 #include "aa_engine.h"
+#include "aa_pool.h"
 
 namespace aa {
 
@@ -85,6 +86,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     // one stage do not alias the operand reads from the other
     __shared__ __attribute__((aligned(16))) char Ks0[KBYTES], Ks1[KBYTES], Vs0[VBYTES], Vs1[VBYTES];
     __shared__ float red[NW];
+    __shared__ float qpart[(FLAGS & kEngStoreState) ? 4 : 1][128];   // pooled-query partial sums (stage 1)
     const KParams& p = a.p;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -394,6 +396,13 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
                     *(floatx4*)(acc + (4 * db + v4) * 256 + 4 * lane) =
                         floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
                                 o[db][4 * v4 + 3] * down};
+        }
+        if (a.qp_hi) {
+            // pooled query of the block (Algorithm 2, avgpool of Q) from the fragments in registers
+            float s0, s1;
+            pool_wave_columns(qf, n, s0, s1);
+            pool_block_finish(qpart, wave, n, hf, s0, s1, tid, rlast - row0 + 1,
+                              blk_index(p, sq, wk.b, wk.h, wk.i), true, a.qp_hi, a.qp_lo, a.qlo_norm);
         }
         if (a.xa) {
             // pooled anchor of the block: mean of M over its rows (Algorithm 2, avgpool of the anchor)

@@ -17,6 +17,7 @@
 // launches this kernel for dense attention and for even `step`, the 128-row kernel otherwise.
 #include "aa_common.h"
 #include "aa_engine.h"
+#include "aa_pool.h"
 
 namespace aa {
 
@@ -77,6 +78,7 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
     __shared__ __attribute__((aligned(16))) char Ks0[KBYTES], Ks1[KBYTES], Ks2[KBYTES];
     __shared__ __attribute__((aligned(16))) char Vs0[VBYTES], Vs1[VBYTES], Vs2[VBYTES];
     __shared__ float red[8];
+    __shared__ float qpart[(FLAGS < 0) ? 2 : 1][(FLAGS < 0) ? 4 : 1][128];   // pooled-query partial sums (stage 1)
     const KParams& p = a.p;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -441,6 +443,15 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
                     *(floatx4*)(acc + (4 * db + v4) * 256 + 4 * lane) =
                         floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
                                 o[db][4 * v4 + 3] * down};
+        }
+        if (FLAGS < 0 && a.qp_hi) {
+            // pooled query of each block (Algorithm 2, avgpool of Q) from the fragments in registers;
+            // the four waves of a block are a team
+            const int blk = (FLAGS < 0) ? chunk >> 2 : 0, b0 = row0 + BQ * blk;
+            float s0, s1;
+            pool_wave_columns(qf, n, s0, s1);
+            pool_block_finish(qpart[blk], chunk & 3, n, hf, s0, s1, 64 * (chunk & 3) + lane, min(b0 + BQ, sq.len) - b0,
+                              blk_index(p, sq, wk.b, wk.h, 2 * wk.i + blk), b0 < sq.len, a.qp_hi, a.qp_lo, a.qlo_norm);
         }
         if (a.xa) {
             // pooled anchor of each block: mean of M over its rows (Algorithm 2, avgpool of the anchor)

@@ -44,6 +44,7 @@ struct SelectArgs {
     float* qlo_norm;          // bf16 path: Euclidean norm of the lo part of each pooled query row
     float* kmax_blk;          // bf16 stripe path: largest key norm per (KV head, key block)
     int is_bf16;              // element type of q, k
+    int pool_skip_q;          // bf16: the pooled queries are there already (stage 1 wrote them)
     unsigned* bits;           // [groups][nwords] selection bit words, bit (j % 32) of word j / 32
     int nwords;               // ceil(N / 32)
     int* segcount;            // [groups][nseg] selected columns per segment of 64 bit words (2048 keys)

@@ -10,6 +10,7 @@
 // the (exactly bf16) keys carry ~16 mantissa bits and the threshold decision does
 // not depend on bf16 rounding of the mean.
 #include "aa_common.h"
+#include "aa_pool.h"
 #include "aa_select.h"
 
 namespace aa {
@@ -29,10 +30,11 @@ __device__ __forceinline__ unsigned short f_to_bf16_rne(float f) {
 }  // namespace
 
 // ------------------------------------------------------------------ pool_q
-// grid (nblk_max, Hq [+ Hkv], B).  bf16: 256 threads, thread (c, rs) sums the 16-byte chunk c of rows
-// rs, rs + 16, ...; writes hi/lo bf16 rows of 128 and the norm of the lo row.  With kmax_blk set the
-// grid has Hkv more rows in y: those work-groups write the largest key norm of their key block
-// (the mask kernel bounds |<lo, k>| by |lo| |k| to decide whether the lo products are needed).
+// grid (nblk_max, Hq [+ Hkv], B).  bf16: 256 threads = the four waves of the tile engines; writes
+// hi/lo bf16 rows of 128 and the norm of the lo row (aa_pool.h).  With kmax_blk set the grid has Hkv
+// more rows in y: those work-groups write the largest key norm of their key block (the mask kernel
+// bounds |<lo, k>| by |lo| |k| to decide whether the lo products are needed).  pool_skip_q: the
+// queries were pooled by stage 1 already, the grid holds the Hkv key rows only.
 // fp32: 128 threads, float rows of d.
 __global__ __launch_bounds__(256) void pool_q_bf16_kernel(SelectArgs a) {
     const KParams& p = a.p;
@@ -43,9 +45,10 @@ __global__ __launch_bounds__(256) void pool_q_bf16_kernel(SelectArgs a) {
     const int r1 = min(r0 + p.bq, sq.len);
     const int tid = threadIdx.x, c = tid & 15, rs = tid >> 4;
     __shared__ float red[16][128];
-    if ((int)blockIdx.y >= p.Hq) {
+    const int y = blockIdx.y + (a.pool_skip_q ? p.Hq : 0);
+    if (y >= p.Hq) {
         // key block i of KV head hk: squared norm of every row (16 threads per row), largest
-        const int hk = blockIdx.y - p.Hq;
+        const int hk = y - p.Hq;
         const unsigned short* src = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, b, hk, 0) + 8 * c;
         float big = 0.f;
         for (int r = r0 + rs; r < r1; r += 16) {
@@ -72,38 +75,25 @@ __global__ __launch_bounds__(256) void pool_q_bf16_kernel(SelectArgs a) {
         }
         return;
     }
-    const int h = blockIdx.y;
-    const unsigned short* src = (const unsigned short*)a.q + tok_offset(p, p.qs, sq, b, h, 0) + 8 * c;
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int r = r0 + rs; r < r1; r += 16) {
-        const uintx4 x = *(const uintx4*)(src + (long long)r * p.qs[2]);
+    // query block i of head h: the fragments of the tile engines (wave w: rows 32 w .. 32 w + 31, lane
+    // (n, hf): the 16-byte pieces 16 ks + 8 hf of row n), pooled by the code the engines use
+    const int h = y;
+    const int lane = tid & 63, wave = tid >> 6, n = lane & 31, hf = lane >> 5;
+    const int r = r0 + 32 * wave + n;
+    bf16x8 qf[8];
+    {
+        const __bf16* src = (const __bf16*)a.q + tok_offset(p, p.qs, sq, b, h, r < r1 ? r : r0);
+        const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            acc[2 * e] += __uint_as_float(x[e] << 16);
-            acc[2 * e + 1] += __uint_as_float(x[e] & 0xffff0000u);
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 x = *(const bf16x8*)(src + 16 * ks + 8 * hf);
+            qf[ks] = r < r1 ? x : zero8;
         }
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) red[rs][8 * c + e] = acc[e];
-    __syncthreads();
-    if (tid < 64) {                                  // two neighbouring columns per thread
-        float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) { s0 += red[k][2 * tid]; s1 += red[k][2 * tid + 1]; }
-        const float inv = 1.f / (float)(r1 - r0);
-        s0 *= inv; s1 *= inv;
-        const unsigned short h0 = f_to_bf16_rne(s0), h1 = f_to_bf16_rne(s1);
-        const unsigned short l0 = f_to_bf16_rne(s0 - bf16_to_f(h0)), l1 = f_to_bf16_rne(s1 - bf16_to_f(h1));
-        const long long bi = blk_index(p, sq, b, h, i);
-        ((unsigned*)a.qp_hi)[bi * 64 + tid] = (unsigned)h0 | ((unsigned)h1 << 16);
-        ((unsigned*)a.qp_lo)[bi * 64 + tid] = (unsigned)l0 | ((unsigned)l1 << 16);
-        // what the hi + lo pair leaves out (below 2^-16 of the entry) is far inside the tolerance of
-        // the decision; the norm of lo bounds what leaving out lo would change
-        float ln = bf16_to_f(l0) * bf16_to_f(l0) + bf16_to_f(l1) * bf16_to_f(l1);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) ln += __shfl_xor(ln, off, 64);
-        if (tid == 0) a.qlo_norm[bi] = sqrtf(ln);
-    }
+    float s0, s1;
+    pool_wave_columns(qf, n, s0, s1);
+    pool_block_finish((float(*)[128])red, wave, n, hf, s0, s1, tid, r1 - r0, blk_index(p, sq, b, h, i), true,
+                      a.qp_hi, a.qp_lo, a.qlo_norm);
 }
 
 __global__ __launch_bounds__(128) void pool_q_fp32_kernel(SelectArgs a) {
