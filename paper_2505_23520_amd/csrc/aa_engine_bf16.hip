@@ -24,55 +24,12 @@
 // exceeds it by more than 2^8; the accumulators (which live in AGPRs) are then
 // rescaled, otherwise they are left alone.  The true row maximum, which is the
 // anchor that stage 1 exports, is tracked separately.
-#include "aa_common.h"
-#include "aa_engine.h"
+#include "aa_engine_bf16_common.h"
 #include "aa_pool.h"
 
 namespace aa {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-
-namespace {
-
-constexpr int D = 128;
-constexpr int BQ = 128;
-constexpr int TK = 64;               // keys per tile
-constexpr int KGRP = 1024 + 16;      // bytes per K group: 4 rows + pad
-constexpr int VGRP = 1024 + 64;      // bytes per V group
-constexpr int KBYTES = 16 * KGRP;
-constexpr int VBYTES = 16 * VGRP;
-constexpr int BUFB = KBYTES + VBYTES; // one stage, bytes
-constexpr float kRescaleLog2 = 8.f;  // raise the reference only for jumps above 2^8
-constexpr floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float floatx8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
-typedef int intx4 __attribute__((ext_vector_type(4)));
-typedef int intx2 __attribute__((ext_vector_type(2)));
-
-typedef short shortx4 __attribute__((ext_vector_type(4)));
-typedef short shortx8 __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) void lds_void;
-
-// s_waitcnt vmcnt(0) only (gfx9 encoding: expcnt and lgkmcnt fields left at their maxima)
-__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
-// x of this lane and x of the lane 32 away, in an order that depends on the half (fine for
-// max and sum); v_permlane32_swap is a plain VALU operation, no trip through the LDS crossbar
-__device__ __forceinline__ void both_halves(float x, float& u, float& v) {
-    const unsigned b = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
-    u = __uint_as_float(r[0]);
-    v = __uint_as_float(r[1]);
-}
-
-}  // namespace
+using namespace eng;
 
 // FLAGS (a combination of kEng*) is a compile-time parameter: every mode gets its own code without
 // the other modes' branches, registers and, above all, merged control-flow paths (where paths with
@@ -188,45 +145,17 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane (n, hf) holds Q[row][16 ks + 8 hf .. +8)
     bf16x8 qf[8];
-    {
-        const __bf16* src = (const __bf16*)a.q + tok_offset(p, p.qs, sq, wk.b, wk.h, rok ? r : 0);
-        const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 x = *(const bf16x8*)(src + 16 * ks + 8 * hf);
-            qf[ks] = rok ? x : zero8;
-        }
-    }
+    load_q_fragments(qf, a, sq, wk.b, wk.h, r, rok, 0, hf);
 
-    // ---- running state, raw dot-product units: reference mref of the exponentials, true
-    // maximum mtrue, per-lane partial row sum l (the two halves of a row are added at the
-    // end), O^T accumulators
+    // ---- running state (see load_state)
     const float c2 = p.sigma * 1.4426950408889634f;  // exp(sigma*x) = exp2(c2*x)
     const float rescale_gap = kRescaleLog2 / c2;
     const long long ri = row_index(p, sq, wk.b, wk.h, rok ? r : row0);
+    const long long tile = acc_tile(p, sq, wk.b, wk.h, wk.i, wave);
     float mref, mtrue, l;
     floatx16 o[4];
-    if (flags & kEngLoadState) {
-        mref = a.Min[ri] / p.sigma;
-        mtrue = mref;
-        l = hf == 0 ? a.Lin[ri] : 0.f;
-        // cached accumulator of this wave's 32 rows, stored in fragment order (see acc_tile)
-        const float* acc = a.Accin + acc_tile(p, sq, wk.b, wk.h, wk.i, wave);
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const floatx4 x = *(const floatx4*)(acc + (4 * db + v4) * 256 + 4 * lane);
-                o[db][4 * v4 + 0] = x.x; o[db][4 * v4 + 1] = x.y;
-                o[db][4 * v4 + 2] = x.z; o[db][4 * v4 + 3] = x.w;
-            }
-    } else {
-        mref = -INFINITY; mtrue = -INFINITY; l = 0.f;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-    }
+    if (flags & kEngLoadState) load_state(a, ri, tile, lane, hf, mref, mtrue, l, o);
+    else init_state(mref, mtrue, l, o);
 
     // ---- pipeline prologue
     if (nT > 0) {
@@ -306,42 +235,8 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
 
         __builtin_amdgcn_s_setprio(0);
-        // online softmax of this lane's query row (the other half of the row is 32 lanes away)
-        float mx = fmaxf(s[0][0], s[1][0]);
-#pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, s[0][v]), s[1][v]);     // v_max3_f32
-        {
-            float u, w;
-            both_halves(mx, u, w);
-            mx = fmaxf(u, w);
-        }
-        mtrue = fmaxf(mtrue, mx);
-        if (__any(mx > mref + rescale_gap)) {                 // rare after the first tiles
-            const float mnew = fmaxf(mref, mx);
-            const float alpha = (mnew == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mnew) * c2);
-            mref = mnew;
-            l *= alpha;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-        }
-        const float mc = (mref == -INFINITY) ? 0.f : mref * c2;
         bf16x8 pf[2][2];  // [kb][s16]
-        float rs = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int h8 = 0; h8 < 2; ++h8) {
-                floatx8 pv;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * h8 + e], c2, -mc));
-                    rs += pv[e];
-                }
-                pf[kb][h8] = __builtin_convertvector(pv, bf16x8);
-            }
-        l += rs;
+        softmax_tile(s, pf, c2, rescale_gap, mref, mtrue, l, o);
 
         __builtin_amdgcn_s_setprio(2);
         // O^T += V^T P^T
@@ -374,29 +269,9 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
     // of one wave execute in order, so no barrier separates its writes from its reads.
     char* const stg = wave == 0 ? Ks0 : wave == 1 ? Ks1 : wave == 2 ? Vs0 : Vs1;
     const int wave_rows = min(32, sq.len - rw);      // rows of this wave inside the sequence (<= 0: none)
-    float lt;                                        // row sum relative to mref
-    {
-        float u, w;
-        both_halves(l, u, w);
-        lt = u + w;
-    }
+    const float lt = row_sum(l);                     // row sum relative to mref
     if (flags & kEngStoreState) {
-        // exported state is relative to the true maximum (Algorithm 1's m, l, acc)
-        const float down = (mref == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mtrue) * c2);
-        const float ms = mtrue * p.sigma;
-        if (rok && hf == 0) { a.Mout[ri] = ms; a.Lout[ri] = lt * down; }
-        if (a.Accout && wave_rows > 0) {
-            // fragment order: every store instruction writes 1 KB of consecutive addresses, and stage 3
-            // reads the tile back the same way (no staging through LDS on either side)
-            float* acc = a.Accout + acc_tile(p, sq, wk.b, wk.h, wk.i, wave);
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4)
-                    *(floatx4*)(acc + (4 * db + v4) * 256 + 4 * lane) =
-                        floatx4{o[db][4 * v4] * down, o[db][4 * v4 + 1] * down, o[db][4 * v4 + 2] * down,
-                                o[db][4 * v4 + 3] * down};
-        }
+        const float ms = store_state(a, ri, tile, rok, wave_rows > 0, lane, hf, c2, mref, mtrue, lt, o);
         if (a.qp_hi) {
             // pooled query of the block (Algorithm 2, avgpool of Q) from the fragments in registers
             float s0, s1;
@@ -418,25 +293,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         }
     }
     if ((flags & kEngStoreOut) && wave_rows > 0) {
-        // the wave's 32 output rows go through LDS (pitch 136 bf16) so that 16 lanes write one
-        // 256-byte row together instead of every lane writing 8-byte pieces of its own row
-        const float inv = 1.f / lt;
-        unsigned short* sb = (unsigned short*)stg;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const floatx4 x = {o[db][4 * v4] * inv, o[db][4 * v4 + 1] * inv, o[db][4 * v4 + 2] * inv,
-                                   o[db][4 * v4 + 3] * inv};
-                *(bf16x4*)(sb + n * 136 + 32 * db + 8 * v4 + 4 * hf) = __builtin_convertvector(x, bf16x4);
-            }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int f = 64 * i + lane, row = f >> 4, c = f & 15;
-            const intx4 x = *(const intx4*)(sb + row * 136 + 8 * c);
-            if (row < wave_rows)
-                *(intx4*)((unsigned short*)a.out + tok_offset(p, p.os, sq, wk.b, wk.h, rw + row) + 8 * c) = x;
-        }
+        store_out(a, stg, tok_offset(p, p.os, sq, wk.b, wk.h, rw), wave_rows, lane, n, hf, lt, o);
         if (rok && a.lse && hf == 0) a.lse[ri] = mref * p.sigma + __logf(lt);
     }
 }
