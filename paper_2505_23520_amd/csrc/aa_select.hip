@@ -211,8 +211,14 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
             blo[ks] = rok ? y : zero8;
         }
     }
-    // theta minus the pooled anchor of the lane's row; -inf = no such row (never selects)
-    const float toff = rok ? p.theta - (p.use_anchor ? a.xa[bi] : 0.f) : -INFINITY;
+    // The threshold test xbar - sigma s <= theta is the sign of s + (theta - xbar) / sigma: that
+    // constant of the lane's row is the initial accumulator of the score MFMAs, so the accumulators
+    // come out as margins (in raw dot-product units) and their sign bits are the decisions.
+    // -inf = no such row (never selects).
+    const float toff = rok ? (p.theta - (p.use_anchor ? a.xa[bi] : 0.f)) / p.sigma : -INFINITY;
+    floatx16 cinit;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) cinit[v] = toff;
     const float lo_norm = rok ? a.qlo_norm[bi] : 0.f;
 
     const unsigned short* kbase = (const unsigned short*)a.k + tok_offset(p, p.ks, sq, b, hk, 0);
@@ -249,7 +255,7 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
         const int J1 = min(chunk1 - 1, sq.len - 1) / p.bq;
         for (int J = chunk0 / p.bq; J <= J1; ++J) kbig = fmaxf(kbig, a.kmax_blk[kb0 + J]);
     }
-    const float lo_bound = 1.001f * p.sigma * lo_norm * kbig;
+    const float lo_bound = 1.001f * lo_norm * kbig;
     // After the tile loop: OR the rows of each group, clip to the group's candidate range, write the
     // bit words of the chunk.  (This stays outside the tile loop: before an inner loop that reads
     // LDS, and before an LDS atomic, the compiler waits for every outstanding asynchronous load
@@ -301,8 +307,8 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
         for (int ks = 0; ks < 8; ++ks) {
             const bf16x8 kf0 = *(const bf16x8*)(Kb + 32 * ks);
             const bf16x8 kf1 = *(const bf16x8*)(Kb + 512 + 32 * ks);
-            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, bhi[ks], ks == 0 ? kZero16 : c[0], 0, 0, 0);
-            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, bhi[ks], ks == 0 ? kZero16 : c[1], 0, 0, 0);
+            c[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, bhi[ks], ks == 0 ? cinit : c[0], 0, 0, 0);
+            c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, bhi[ks], ks == 0 ? cinit : c[1], 0, 0, 0);
         }
         // operand reads run ahead of their MFMAs
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
@@ -313,17 +319,12 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
         __builtin_amdgcn_s_setprio(0);
-        // Threshold test xbar - sigma s <= theta as the sign of sigma s + (theta - xbar).
-        float mg[2][16];
         float nearest = INFINITY;                    // smallest |margin| of the lane's 32 scores
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                mg[kb][v] = fmaf(p.sigma, c[kb][v], toff);
-                mg[kb][v + 1] = fmaf(p.sigma, c[kb][v + 1], toff);
-                nearest = fminf(fminf(nearest, fabsf(mg[kb][v])), fabsf(mg[kb][v + 1]));     // v_min3_f32
-            }
+            for (int v = 0; v < 16; v += 2)
+                nearest = fminf(fminf(nearest, fabsf(c[kb][v])), fabsf(c[kb][v + 1]));       // v_min3_f32
         if (__any(nearest <= lo_bound)) {
             // some decision of this wave's tile hangs on the lo products: add them (rare: only
             // margins within ~1e-2 of zero get here)
@@ -336,22 +337,20 @@ __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
                 c[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, blo[ks], c[1], 0, 0, 0);
             }
             __builtin_amdgcn_s_setprio(0);
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mg[kb][v] = fmaf(p.sigma, c[kb][v], toff);
         }
         // Sign bits shifted into a word (one instruction per score, no compare / select chains).
         // The lane gathers the bits of its 16 keys per 32-key block (accumulator register v holds
-        // key 8 (v / 4) + 4 hf + v % 4), the other half of the wave holds the remaining 16.
+        // key 8 (v / 4) + 4 hf + v % 4, i.e. its nibbles alternate with those of the lane 32 away,
+        // which holds the other 16 keys of the same row).
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             unsigned neg = 0;                        // bit v = sign of score v's margin
 #pragma unroll
             for (int v = 15; v >= 0; --v)
-                neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(mg[kb][v]), 31);
-            const unsigned sel = ~neg & 0xffffu;
-            unsigned wd = (sel & 0xfu) | ((sel & 0xf0u) << 4) | ((sel & 0xf00u) << 8) | ((sel & 0xf000u) << 12);
+                neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(c[kb][v]), 31);
+            unsigned wd = ~neg & 0xffffu;
+            wd = (wd | (wd << 8)) & 0x00ff00ffu;     // nibble i of the 16 bits -> nibble 2 i of the word
+            wd = (wd | (wd << 4)) & 0x0f0f0f0fu;
             wd <<= 4 * hf;
             const auto both = __builtin_amdgcn_permlane32_swap(wd, wd, false, false);
             if (hf == 0) rowword[t][lr][kb] = both[0] | both[1];
