@@ -278,8 +278,10 @@ int run_anchor(const Plan& pl, const aa_params* p, const void* q, const void* k,
 }
 
 // q_pooled: stage 1 has written the pooled queries into ws already (bf16 only)
+// stats (nullable): the scan kernel also reports attended pairs and selected entries there
 int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k, const float* xa, int32_t* counts,
-               int64_t* offsets, int32_t* idx, int64_t cap, int32_t* flag, char* ws, bool q_pooled, hipStream_t st) {
+               int64_t* offsets, int32_t* idx, int64_t cap, int32_t* flag, char* ws, bool q_pooled, int64_t* stats,
+               hipStream_t st) {
     const KParams& kp = pl.kp;
     SelectArgs sa;
     memset(&sa, 0, sizeof(sa));
@@ -297,6 +299,7 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
     sa.counts = counts; sa.offsets = (long long*)offsets; sa.idx = idx;
     sa.idx_capacity = cap; sa.overflow = flag;
     sa.groups_total = pl.sz.groups;
+    sa.stats = (long long*)stats;
 
     const dim3 gblk(kp.nblk_max, kp.Hq, kp.B), ggrp(kp.ngrp_max, kp.Hq, kp.B);
     if (p->granularity == AA_BLOCK) AA_HIP(raise_lds_limits());   // before anything is enqueued
@@ -349,26 +352,6 @@ int run_sparse(const Plan& pl, const aa_params* p, const void* q, const void* k,
     return launch_engine(pl, p, ea, st);
 }
 
-// stats[0] += attended pairs, stats[1] += selected entries.  grid (ngrp_max, Hq, B), 64 threads.
-__global__ __launch_bounds__(64) void stats_kernel(KParams p, const int* counts, unsigned long long* stats) {
-    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const Seq sq = seq_of(p, b);
-    const int span = p.bq * p.step;
-    if ((long long)g * span >= sq.len) return;
-    const int W = window_start(p, g);
-    const int r0 = g * span, r1 = min(r0 + span, sq.len);
-    const int cnt = counts[grp_index(p, sq, b, h, g)];
-    unsigned long long pairs = 0;
-    for (int r = r0 + threadIdx.x; r < r1; r += 64)
-        pairs += (unsigned long long)(min(p.n_init, r + 1) + max(0, r - W + 1) + cnt);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) pairs += __shfl_xor(pairs, off, 64);
-    if (threadIdx.x == 0) {
-        atomicAdd(&stats[0], pairs);
-        atomicAdd(&stats[1], (unsigned long long)cnt);
-    }
-}
-
 // register-only MFMA loop (see anchor_probe_mfma)
 typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
@@ -386,10 +369,6 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
     for (int i = 0; i < 4; ++i)
         for (int v = 0; v < 16; ++v) s += c[i][v];
     sink[blockIdx.x * 256 + threadIdx.x] = s;
-}
-
-__global__ void zero_u64_kernel(unsigned long long* x, int nelem) {
-    if ((int)threadIdx.x < nelem) x[threadIdx.x] = 0ull;
 }
 
 }  // namespace
@@ -437,7 +416,7 @@ int stripe_select(const aa_params* params, const void* q, const void* k, const f
     if (idx_capacity < 0 || misaligned(q) || misaligned(k) || misaligned(idx) || misaligned(ws)) return AA_EINVAL;
     if (ws_bytes < pl.sz.select_ws_bytes) return AA_EWORKSPACE;
     return run_select(pl, params, q, k, xa_pooled, counts, offsets, idx, idx_capacity, overflow_flag, (char*)ws,
-                      false, (hipStream_t)stream);
+                      false, nullptr, (hipStream_t)stream);
 }
 
 int stripe_select_noalloc(const aa_params* params, const void* q, const void* k, const float* xa_pooled,
@@ -453,7 +432,7 @@ int stripe_select_noalloc(const aa_params* params, const void* q, const void* k,
     rc = scratch_of_current_device(&ws);
     if (rc != AA_OK) return rc;
     return run_select(pl, params, q, k, xa_pooled, counts, offsets, idx, idx_capacity, overflow_flag, (char*)ws,
-                      false, (hipStream_t)stream);
+                      false, nullptr, (hipStream_t)stream);
 }
 
 int sparse_attn(const aa_params* params, const void* q, const void* k, const void* v, const float* M, const float* L,
@@ -493,15 +472,10 @@ int anchor_attention_prefill(const aa_params* params, const void* q, const void*
     // queries in registers; the stage-wise entry points compute the same bits in a kernel of their own
     rc = run_anchor(pl, params, q, k, v, M, L, Acc, xa, w + pl.pf_sel, st);
     if (rc != AA_OK) return rc;
-    rc = run_select(pl, params, q, k, xa, counts, offsets, idx, pl.sz.idx_capacity_max, flag, w + pl.pf_sel, true, st);
+    rc = run_select(pl, params, q, k, xa, counts, offsets, idx, pl.sz.idx_capacity_max, flag, w + pl.pf_sel, true, stats, st);
     if (rc != AA_OK) return rc;
     rc = run_sparse(pl, params, q, k, v, M, L, Acc, counts, offsets, idx, pl.sz.idx_capacity_max, out, lse, st);
     if (rc != AA_OK) return rc;
-    if (stats) {
-        AA_LAUNCH(zero_u64_kernel, dim3(1), dim3(64), 0, st, (unsigned long long*)stats, 4);
-        AA_LAUNCH(stats_kernel, dim3(pl.kp.ngrp_max, pl.kp.Hq, pl.kp.B), dim3(64), 0, st, pl.kp, (const int*)counts,
-                  (unsigned long long*)stats);
-    }
     return AA_OK;
 }
 

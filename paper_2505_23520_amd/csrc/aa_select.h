@@ -55,6 +55,7 @@ struct SelectArgs {
     long long idx_capacity;
     int* overflow;
     long long groups_total;
+    long long* stats;         // nullable, int64[4]: { attended pairs, selected entries, 0, 0 }
     // bf16 mask kernel: work items per (sequence, KV head) pair for the longest sequence, total
     // work-groups, and work-groups per XCD (see mask_bf16_kernel)
     int mask_items;

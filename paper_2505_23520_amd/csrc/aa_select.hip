@@ -581,14 +581,52 @@ __global__ __launch_bounds__(256) void count_kernel(SelectArgs a) {
     if (threadIdx.x == 0) a.counts[t] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
 }
 
-// one work-group of 1024 threads: offsets[t] = sum_{t' < t} roundup64(counts[t'])
+// one work-group of 1024 threads: offsets[t] = sum_{t' < t} roundup64(counts[t']).  With a.stats set
+// it also adds up what the prefill reports: attended (row, key) pairs = every row's anchor region
+// (closed form per group) plus its group's list, and the selected entries.
+namespace {
+__device__ __forceinline__ long long tri(long long m) { return m > 0 ? m * (m + 1) / 2 : 0; }
+// pairs of the anchor regions of the rows r0 .. r1-1 of a group with window start W:
+// sum over r of min(n_init, r + 1) + max(0, r - W + 1)
+__device__ __forceinline__ long long anchor_pairs(long long n_init, long long W, long long r0, long long r1) {
+    const long long e = min(r1, n_init);
+    long long s = e > r0 ? tri(e) - tri(r0) : 0;            // rows inside the initial tokens see r + 1 of them
+    s += n_init * max(0ll, r1 - max(r0, n_init));           // later rows see all of them
+    s += tri(r1 - W) - tri(r0 - W);                         // window: W .. r
+    return s;
+}
+}  // namespace
+
 __global__ __launch_bounds__(1024) void scan_kernel(SelectArgs a) {
+    const KParams& p = a.p;
     const long long T = a.groups_total;
     const int tid = threadIdx.x;
     const long long per = (T + 1023) / 1024;
     const long long lo = min(T, per * tid), hi = min(T, lo + per);
-    long long s = 0;
-    for (long long t = lo; t < hi; ++t) s += (a.counts[t] + kIdxPad - 1) / kIdxPad * (long long)kIdxPad;
+    long long s = 0, pairs = 0, entries = 0;
+    for (long long t = lo; t < hi; ++t) {
+        const int cnt = a.counts[t];
+        s += (cnt + kIdxPad - 1) / kIdxPad * (long long)kIdxPad;
+        if (a.stats) {
+            // group t -> (sequence, group in the sequence); slots past a packed batch's groups hold 0
+            const long long slot = t % p.grp_cap;
+            const long long span = (long long)p.bq * p.step;
+            long long len = p.N, g = slot;
+            if (p.packed) {
+                len = 0;
+                for (int b = 0; b < p.B; ++b) {
+                    const long long n = p.cu[b + 1] - p.cu[b], ng = (n + span - 1) / span;
+                    if (g < ng) { len = n; break; }
+                    g -= ng;
+                }
+            }
+            if (g * span < len) {
+                const long long r0 = g * span, r1 = min(r0 + span, len);
+                pairs += anchor_pairs(p.n_init, window_start(p, (int)g), r0, r1) + (r1 - r0) * cnt;
+                entries += cnt;
+            }
+        }
+    }
     __shared__ long long part[1024];
     part[tid] = s;
     __syncthreads();
@@ -606,6 +644,22 @@ __global__ __launch_bounds__(1024) void scan_kernel(SelectArgs a) {
     if (tid == 1023) {
         a.offsets[T] = part[1023];
         if (a.overflow) *a.overflow = part[1023] > a.idx_capacity ? 1 : 0;
+    }
+    if (a.stats) {                                           // block sums of pairs and entries
+        __syncthreads();
+        for (int pass = 0; pass < 2; ++pass) {
+            long long x = pass ? entries : pairs;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+            if ((tid & 63) == 0) part[pass * 16 + (tid >> 6)] = x;
+        }
+        __syncthreads();
+        if (tid < 4) {
+            long long x = 0;
+            if (tid < 2)
+                for (int w = 0; w < 16; ++w) x += part[tid * 16 + w];
+            a.stats[tid] = x;
+        }
     }
 }
 
