@@ -321,10 +321,9 @@ int run_select(const Plan& pl, const aa_params* p, const void* q, const void* k,
         // one work-group per (query head, row tile, key chunk with candidates); the longest
         // sequence bounds every other
         sa.mask_items = mask_pair_items(kp.nblk_max, kp.step, kp.bq, kp.w, kp.n_init);
-        sa.mask_total = (long long)sa.mask_items * kp.Hq * kp.B;
-        sa.mask_per_xcd = cdiv(sa.mask_total, 8);
-        if (sa.mask_per_xcd * 8 > 0x7fffffffll) return AA_EUNSUPPORTED;
-        const dim3 gm((unsigned)(sa.mask_per_xcd > 0 ? sa.mask_per_xcd * 8 : 8));
+        const long long mask_per_xcd = cdiv((long long)sa.mask_items * kp.Hq * kp.B, 8);
+        if (mask_per_xcd * 8 > 0x7fffffffll) return AA_EUNSUPPORTED;
+        const dim3 gm((unsigned)(mask_per_xcd > 0 ? mask_per_xcd * 8 : 8));
         AA_LAUNCH(mask_bf16_kernel, gm, dim3(256), 0, st, sa);
     } else {
         AA_LAUNCH(pool_q_fp32_kernel, gblk, dim3(128), 0, st, sa);

@@ -56,10 +56,8 @@ struct SelectArgs {
     int* overflow;
     long long groups_total;
     long long* stats;         // nullable, int64[4]: { attended pairs, selected entries, 0, 0 }
-    // bf16 mask kernel: work items per (sequence, KV head) pair for the longest sequence, total
-    // work-groups, and work-groups per XCD (see mask_bf16_kernel)
+    // bf16 mask kernel: work items per (sequence, KV head) pair for the longest sequence (sizes the grid)
     int mask_items;
-    long long mask_total, mask_per_xcd;
 };
 
 __global__ void pool_q_bf16_kernel(SelectArgs a);

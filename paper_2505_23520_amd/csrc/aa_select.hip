@@ -126,8 +126,9 @@ __global__ __launch_bounds__(128) void pool_q_fp32_kernel(SelectArgs a) {
 // tokens -- and is read from HBM once if those run at the same time on one XCD (each XCD has its
 // own L2).  The hardware deals consecutive work-group ids round-robin to the 8 XCDs, so id
 // -> logical index L = (id % 8) * per_xcd + id / 8 gives each XCD a contiguous range of L, walked
-// in order; L enumerates (sequence, KV head) pairs, inside a pair the key chunks in ascending
-// order, inside a chunk the row tiles that need it, and the query heads of the KV head fastest.
+// in order; L enumerates sequences, inside a sequence the KV heads, inside a (sequence, KV head)
+// pair the key chunks in ascending order, inside a chunk the row tiles that need it, and the
+// query heads of the KV head fastest.
 constexpr int kMaskTileKeys = 64;
 constexpr int kMaskChunkTiles = kMaskChunkKeys / kMaskTileKeys;   // tiles per work-group
 constexpr int kKGrp = 1024 + 16;                         // bytes per group of four K rows + pad
@@ -147,11 +148,38 @@ __device__ __forceinline__ void lds_barrier() {
 
 __global__ __launch_bounds__(256, 3) void mask_bf16_kernel(SelectArgs a) {
     const KParams& p = a.p;
-    const long long L = (long long)(blockIdx.x & 7u) * a.mask_per_xcd + (blockIdx.x >> 3);
-    if ((blockIdx.x >> 3) >= a.mask_per_xcd || L >= a.mask_total) return;
-    const int per_pair = a.mask_items * p.grp;
-    const int pr = (int)(L / per_pair), e = (int)(L % per_pair);
-    const int b = pr / p.Hkv, hk = pr % p.Hkv, h = hk * p.grp + e % p.grp;
+    // Work items that exist: per sequence, items(len) x Hq (a packed batch's shorter sequences have
+    // fewer than the longest one, for which the host sized the grid).  Every XCD gets an equal,
+    // contiguous share of them, so the load is balanced whatever the mix of lengths.
+    const int span_blk = p.bq;
+    long long real = 0;
+    if (p.packed) {
+        for (int s = 0; s < p.B; ++s)
+            real += mask_pair_items((p.cu[s + 1] - p.cu[s] + span_blk - 1) / span_blk, p.step, p.bq, p.w, p.n_init);
+        real *= p.Hq;
+    } else {
+        real = (long long)a.mask_items * p.Hq * p.B;
+    }
+    const long long per_xcd = (real + 7) / 8;
+    const long long slot = blockIdx.x >> 3;
+    long long L = (long long)(blockIdx.x & 7u) * per_xcd + slot;
+    if (slot >= per_xcd || L >= real) return;
+    // L -> sequence b, then inside the sequence KV head, item, query head of the KV head
+    int b = 0, items_b = a.mask_items;
+    if (p.packed) {
+        for (;; ++b) {
+            items_b = mask_pair_items((p.cu[b + 1] - p.cu[b] + span_blk - 1) / span_blk, p.step, p.bq, p.w, p.n_init);
+            const long long n = (long long)items_b * p.Hq;
+            if (L < n) break;
+            L -= n;
+        }
+    } else {
+        b = (int)(L / ((long long)items_b * p.Hq));
+        L -= (long long)b * items_b * p.Hq;
+    }
+    const int per_pair = items_b * p.grp;
+    const int hk = (int)(L / per_pair), e = (int)(L % per_pair);
+    const int h = hk * p.grp + e % p.grp;
     const Seq sq = seq_of(p, b);
     const int nblk = (sq.len + p.bq - 1) / p.bq;
     const int RT = mask_row_tile(p.step);
