@@ -308,6 +308,20 @@ def test_packed_varlen(api):
         assert worst["selected"] > 0
 
 
+def test_packed_many_sequences_some_without_candidates(api):
+    """Six packed sequences, three of them too short to have any candidate column (the mask kernel
+    deals only the work items that exist to its work-groups and has to step over such sequences)."""
+    lens = [100, 5000, 64, 3000, 129, 2600]
+    wl = _wl("t", "bf16", lens, 4, 2, 128, 128, 81, 24)
+    cfg = api.Config(block=128, n_init=128, window=128, step=2, theta=4.5)
+    run, worst = _run_and_check(api, wl, cfg, packed=True)
+    assert 0 < worst["selected"] < worst["candidates"]
+    counts = run.buf["counts"].cpu().numpy()
+    for b in (0, 2, 4):                              # one group, no candidates: empty lists
+        for h in range(4):
+            assert counts[run.grp_index(b, h, 0)] == 0
+
+
 def test_fixed_batch_and_strided_layout(api):
     """B = 2 fixed-length batch; tensors given as [B, N, H, d] views (token-major memory)."""
     from parity_util import DeviceRun, check_groups
