@@ -236,7 +236,8 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
 
         __builtin_amdgcn_s_setprio(0);
         bf16x8 pf[2][2];  // [kb][s16]
-        softmax_tile(s, pf, c2, rescale_gap, mref, mtrue, l, o);
+        if constexpr ((FLAGS & kEngStoreState) != 0) softmax_tile(s, pf, c2, rescale_gap, mref, mtrue, l, o);
+        else softmax_tile_lazy(s, pf, c2, mref, l, o);
 
         __builtin_amdgcn_s_setprio(2);
         // O^T += V^T P^T

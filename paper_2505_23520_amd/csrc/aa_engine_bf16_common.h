@@ -135,6 +135,63 @@ __device__ __forceinline__ void softmax_tile(const floatx16 (&s)[2], bf16x8 (&pf
     l += rs;
 }
 
+// The same for the modes that do not export the true row maximum (stage 3, dense attention): the
+// maximum is only looked for when it is needed.  The probabilities are computed against the
+// current reference straight away; only if some lane's partial row sum shows a probability above
+// 2^8 (or infinite), or some row has no reference yet (the first tiles), the wave
+// finds the row maxima, raises the references, rescales the accumulators and computes the tile's
+// probabilities again (wave-uniform branch, rare after the first tiles).
+__device__ __forceinline__ void softmax_tile_lazy(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], float c2, float& mref,
+                                                  float& l, floatx16 (&o)[4]) {
+    float mc = (mref == -INFINITY) ? 0.f : mref * c2;
+    float rs = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int h8 = 0; h8 < 2; ++h8) {
+            floatx8 pv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * h8 + e], c2, -mc));
+                rs += pv[e];
+            }
+            pf[kb][h8] = __builtin_convertvector(pv, bf16x8);
+        }
+    if (__any(rs > 256.f || mref == -INFINITY)) {
+        float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, s[0][v]), s[1][v]);
+        {
+            float u, w;
+            both_halves(mx, u, w);
+            mx = fmaxf(u, w);
+        }
+        const float mnew = fmaxf(mref, mx);
+        const float alpha = (mnew == -INFINITY || mref == mnew) ? 1.f : __builtin_amdgcn_exp2f((mref - mnew) * c2);
+        mref = mnew;
+        l *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        mc = (mref == -INFINITY) ? 0.f : mref * c2;
+        rs = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int h8 = 0; h8 < 2; ++h8) {
+                floatx8 pv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    pv[e] = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * h8 + e], c2, -mc));
+                    rs += pv[e];
+                }
+                pf[kb][h8] = __builtin_convertvector(pv, bf16x8);
+            }
+    }
+    l += rs;
+}
+
 // Row sum of the whole row (both halves), relative to mref.
 __device__ __forceinline__ float row_sum(float l) {
     float u, w;

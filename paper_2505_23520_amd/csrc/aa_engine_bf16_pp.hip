@@ -269,7 +269,8 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
                     s[kb][v] = ok ? s[kb][v] : -INFINITY;
                 }
         }
-        softmax_tile(s, pf, c2, rescale_gap, mref, mtrue, l, o);
+        if constexpr (FLAGS < 0 || (FLAGS & kEngStoreState) != 0) softmax_tile(s, pf, c2, rescale_gap, mref, mtrue, l, o);
+        else softmax_tile_lazy(s, pf, c2, mref, l, o);
     };
 
     // ---- The MFMA phase always runs, also for a tile this wave skips (P = 0) and for the padding
