@@ -269,8 +269,13 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
                     s[kb][v] = ok ? s[kb][v] : -INFINITY;
                 }
         }
-        if constexpr (FLAGS < 0 || (FLAGS & kEngStoreState) != 0) softmax_tile(s, pf, c2, rescale_gap, mref, mtrue, l, o);
-        else softmax_tile_lazy(s, pf, c2, mref, l, o);
+        // The lazy variant (row maximum only when needed) is used for dense attention alone.  With
+        // lists it measured slower in this kernel although it issues fewer instructions: at 128k with
+        // every column selected the launch then fetches 240 GiB from HBM instead of 19 GiB (the
+        // work-groups that share one KV head's stream through an XCD's L2 no longer stay within its
+        // 4 MB of each other), 110.0 ms against 108.7 ms.
+        if constexpr (FLAGS == (kEngAnchorRegion | kEngDense | kEngStoreOut)) softmax_tile_lazy(s, pf, c2, mref, l, o);
+        else softmax_tile(s, pf, c2, rescale_gap, mref, mtrue, l, o);
     };
 
     // ---- The MFMA phase always runs, also for a tile this wave skips (P = 0) and for the padding
