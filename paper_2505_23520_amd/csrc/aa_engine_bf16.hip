@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void engine_bf16_kernel(EngineArgs a) {
         // (the work-group still needs it for its later rows): nothing to compute
         if (!(t < nA && t0 > rw + 31)) {
         floatx16 s[2];
-        if (mode == 0) {
+        if (__builtin_expect(mode == 0, 1)) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 const bf16x8 kf = *(const bf16x8*)(Kb + 512 * kb);

@@ -108,7 +108,7 @@ __device__ __forceinline__ void softmax_tile(const floatx16 (&s)[2], bf16x8 (&pf
         mx = fmaxf(u, w);
     }
     mtrue = fmaxf(mtrue, mx);
-    if (__any(mx > mref + rescale_gap)) {
+    if (__builtin_expect(__any(mx > mref + rescale_gap), 0)) {
         const float mnew = fmaxf(mref, mx);
         const float alpha = (mnew == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((mref - mnew) * c2);
         mref = mnew;
@@ -157,7 +157,7 @@ __device__ __forceinline__ void softmax_tile_lazy(const floatx16 (&s)[2], bf16x8
             }
             pf[kb][h8] = __builtin_convertvector(pv, bf16x8);
         }
-    if (__any(rs > 256.f || mref == -INFINITY)) {
+    if (__builtin_expect(__any(rs > 256.f || mref == -INFINITY), 0)) {
         float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
         for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, s[0][v]), s[1][v]);

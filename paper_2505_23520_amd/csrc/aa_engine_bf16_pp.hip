@@ -249,13 +249,13 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
     // entry jl of the last list chunk is real iff jl < rem; hidden scores count as -inf.  The
     // hidden scores are overwritten in place before the common code.
     auto softmax_phase = [&](int t) {
-        if (!tile_on(t)) {
+        if (__builtin_expect(!tile_on(t), 0)) {
             const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
             pf[0][0] = zero8; pf[0][1] = zero8; pf[1][0] = zero8; pf[1][1] = zero8;
             return;
         }
         const int mode = tile_mode(t);
-        if (mode != 0) {
+        if (__builtin_expect(mode != 0, 0)) {
             const int t0 = mode == 1 ? tile_start(t) : 0;
             const int jr = mode == 1 ? r - t0 : cnt - (t - nA) * TK - 1;
             const int jn = mode == 1 ? ninit - t0 : TK;
@@ -269,12 +269,14 @@ __global__ __launch_bounds__(512, 1) void engine_bf16_pp_kernel(EngineArgs a) {
                     s[kb][v] = ok ? s[kb][v] : -INFINITY;
                 }
         }
-        // The lazy variant (row maximum only when needed) is used for dense attention alone.  With
-        // lists it measured slower in this kernel although it issues fewer instructions: at 128k with
-        // every column selected the launch then fetches 240 GiB from HBM instead of 19 GiB (the
-        // work-groups that share one KV head's stream through an XCD's L2 no longer stay within its
-        // 4 MB of each other), 110.0 ms against 108.7 ms.
-        if constexpr (FLAGS == (kEngAnchorRegion | kEngDense | kEngStoreOut)) softmax_tile_lazy(s, pf, c2, mref, l, o);
+        // The lazy variant (row maximum only when needed) wherever the true maximum is not exported.
+        // Its rare branch, like the other rare branches of the tile loop, is marked unlikely: the
+        // compiler then lays the loop body out compactly, and that decides more than instruction
+        // count here.  With the rescue code inside the loop body the launch with lists (128k, every
+        // column selected) fetched 240 GiB from HBM instead of 19 GiB and ran slower than the eager
+        // form: the work-groups that share one KV head's stream through an XCD's L2 no longer kept
+        // within its 4 MB of each other.
+        if constexpr (FLAGS >= 0 && (FLAGS & kEngStoreState) == 0) softmax_tile_lazy(s, pf, c2, mref, l, o);
         else softmax_tile(s, pf, c2, rescale_gap, mref, mtrue, l, o);
     };
 
