@@ -368,12 +368,13 @@ def sustained_rates(api, torch, log):
     """Rates this GPU sustains at its actual clock: register-only MFMA loop, 1 GiB device copies
     (the copies are also the dispatches of known size that scale the FETCH_SIZE / WRITE_SIZE
     counters of a rocprofv3 --pmc run of this same command)."""
+    from paper_2505_23520_amd import probe
     scratch = torch.empty(1 << 18, dtype=torch.float32, device="cuda")
-    api.anchor_probe_mfma(200, scratch)
+    probe.mfma_probe(200, scratch)
     torch.cuda.synchronize()
     p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     p0.record()
-    flop = api.anchor_probe_mfma(10000, scratch)
+    flop = probe.mfma_probe(10000, scratch)
     p1.record()
     torch.cuda.synchronize()
     mfma = flop / (p0.elapsed_time(p1) * 1e-3)

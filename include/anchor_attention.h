@@ -220,15 +220,6 @@ int anchor_attention_prefill(const aa_params *params, const void *q, const void 
 int dense_causal_flash(const aa_params *params, const void *q, const void *k, const void *v,
                        void *out, float *lse, void *stream);
 
-/*
- * Measurement aid (not part of the method): enqueues a register-only loop of
- * v_mfma_f32_32x32x16_bf16 on 1024 work-groups of 4 waves, `iters` x 16 MFMAs per wave, i.e.
- * 1024 * 4 * iters * 16 * 32768 FLOP.  Timing it with events on `stream` gives the bf16 MFMA
- * rate this GPU sustains at its actual clock, next to which the attention kernels are quoted.
- * scratch: device buffer of at least 1 MiB (receives one float per thread).
- */
-int anchor_probe_mfma(int iters, void *scratch, void *stream);
-
 const char *anchor_strerror(int code);
 /* Text of the last HIP error this thread's calls ran into ("" if none). */
 const char *anchor_last_hip_error(void);

@@ -58,7 +58,6 @@ _SIGNATURES = {
     "sparse_attn": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, _P, _P, _P, ctypes.c_int64, _P, _P, _P]),
     "anchor_attention_prefill": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P, _P, ctypes.c_size_t, _P]),
     "dense_causal_flash": (ctypes.c_int, [_PP, _P, _P, _P, _P, _P, _P]),
-    "anchor_probe_mfma": (ctypes.c_int, [ctypes.c_int, _P, _P]),
     "anchor_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "anchor_last_hip_error": (ctypes.c_char_p, []),
 }
@@ -203,12 +202,6 @@ def anchor_attention_prefill(p, q, k, v, out, lse, stats, ws, stream=None):
 def dense_causal_flash(p, q, k, v, out, lse=None, stream=None):
     _check(_lib.dense_causal_flash(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse),
                                    _stream(stream)))
-
-
-def anchor_probe_mfma(iters, scratch, stream=None):
-    """Enqueue the register-only MFMA loop; returns the FLOP it performs."""
-    _check(_lib.anchor_probe_mfma(int(iters), _ptr(scratch), _stream(stream)))
-    return 1024 * 4 * int(iters) * 16 * 32768.0
 
 
 def alloc_stage_buffers(p: aa_params, device="cuda", want_acc=True, idx_capacity=None) -> dict:

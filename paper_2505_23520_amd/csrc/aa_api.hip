@@ -351,25 +351,6 @@ int run_sparse(const Plan& pl, const aa_params* p, const void* q, const void* k,
     return launch_engine(pl, p, ea, st);
 }
 
-// register-only MFMA loop (see anchor_probe_mfma)
-typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
-typedef float probe_floatx16 __attribute__((ext_vector_type(16)));
-__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink) {
-    probe_floatx16 c[4];
-    for (int i = 0; i < 4; ++i)
-        for (int v = 0; v < 16; ++v) c[i][v] = threadIdx.x * 1e-3f;
-    probe_bf16x8 x, y;
-    for (int i = 0; i < 8; ++i) { x[i] = (__bf16)(threadIdx.x * 0.001f); y[i] = (__bf16)(i * 0.01f); }
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) c[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, c[i & 3], 0, 0, 0);
-    }
-    float s = 0.f;
-    for (int i = 0; i < 4; ++i)
-        for (int v = 0; v < 16; ++v) s += c[i][v];
-    sink[blockIdx.x * 256 + threadIdx.x] = s;
-}
-
 }  // namespace
 }  // namespace aa
 
@@ -492,12 +473,6 @@ int dense_causal_flash(const aa_params* params, const void* q, const void* k, co
     ea.q = q; ea.k = k; ea.v = v;
     ea.out = out; ea.lse = lse;
     return launch_engine(pl, params, ea, (hipStream_t)stream);
-}
-
-int anchor_probe_mfma(int iters, void* scratch, void* stream) {
-    if (iters <= 0 || !scratch) return AA_EINVAL;
-    AA_LAUNCH(probe_mfma_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream, iters, (float*)scratch);
-    return AA_OK;
 }
 
 const char* anchor_strerror(int code) {

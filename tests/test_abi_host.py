@@ -37,6 +37,17 @@ def test_header_symbols_are_exported(api):
         assert getattr(lib, name) is not None
 
 
+def test_probe_library_is_separate_from_the_product(api):
+    """bench.py's MFMA-rate probe lives in its own shared object; the attention library does not export it."""
+    from paper_2505_23520_amd import probe
+    lib = ctypes.CDLL(probe.LIB_PATH)
+    for name in probe.EXPORTS:
+        assert getattr(lib, name) is not None
+        assert not hasattr(ctypes.CDLL(api.LIB_PATH), name)
+    assert probe._lib.anchor_probe_mfma_flop(3) == 1024 * 4 * 3 * 16 * 32768.0
+    assert probe._lib.anchor_probe_mfma(0, None, None) == -1        # rejected on the host, nothing launched
+
+
 def test_sizes_arithmetic(api):
     s = api.anchor_sizes(_params(api))
     assert s.rows == 32 * 8192 and s.acc_elems == s.rows * 128
