@@ -36,7 +36,8 @@
  *  Packed variable-length batches (cu_seqlens != NULL): sequence b holds tokens
  *  cu_seqlens[b] .. cu_seqlens[b+1]-1 of a packed token axis; stride[0] is
  *  ignored, r is replaced by cu_seqlens[b] + r, N is the longest sequence and
- *  total_tokens = cu_seqlens[B].
+ *  total_tokens = cu_seqlens[B].  A sequence may be empty (cu_seqlens[b] ==
+ *  cu_seqlens[b+1]): it owns no rows, blocks or groups.
  *
  *  Per-row arrays (M, L, lse), float:
  *      fixed length: row (b,h,r) at (b*Hq + h)*N + r

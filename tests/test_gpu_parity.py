@@ -308,6 +308,24 @@ def test_packed_varlen(api):
         assert worst["selected"] > 0
 
 
+def test_packed_batch_with_empty_sequences(api):
+    """cu_seqlens may repeat a value: such a sequence owns no rows, blocks or groups, and the others
+    are laid out and computed as if it were not there (first, middle and last position)."""
+    for dtype, d, block, lens in (("bf16", 128, 128, [0, 700, 0, 0, 1500, 0]), ("fp32", 64, 32, [0, 200, 0, 333])):
+        wl = _wl("t", dtype, lens, 4, 2, d, block, 82, 12)
+        cfg = api.Config(block=block, n_init=block, window=block, step=2, theta=4.5)
+        run, worst = _run_and_check(api, wl, cfg, packed=True)
+        assert worst["selected"] > 0
+        # the same sequences without the empty ones: identical output rows
+        keep = [s for s in range(len(lens)) if lens[s] > 0]
+        wl2 = _wl("t", dtype, lens, 4, 2, d, block, 82, 12)
+        from parity_util import DeviceRun
+        seqs = [synth.make_sequence(wl2, s, signal="logit") for s in keep]
+        run2 = DeviceRun(api, seqs, cfg, dtype, packed=True).stages()
+        assert torch.equal(run.out, run2.out)
+        assert torch.equal(run.buf["lse"], run2.buf["lse"])
+
+
 def test_packed_many_sequences_some_without_candidates(api):
     """Six packed sequences, three of them too short to have any candidate column (the mask kernel
     deals only the work items that exist to its work-groups and has to step over such sequences)."""
