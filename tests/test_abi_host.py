@@ -37,6 +37,21 @@ def test_header_symbols_are_exported(api):
         assert getattr(lib, name) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own, and the struct the binding
+    declares has the size the C compiler gives it."""
+    import subprocess
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "anchor_attention.h"\n#include <stdio.h>\n'
+                   'int main(void) { printf("%zu %zu\\n", sizeof(aa_params), sizeof(aa_sizes)); return 0; }\n')
+    exe = tmp_path / "hdr"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror",
+                           "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    sizes = subprocess.check_output([str(exe)], text=True).split()
+    from paper_2505_23520_amd import api as _api
+    assert [int(x) for x in sizes] == [ctypes.sizeof(_api.aa_params), ctypes.sizeof(_api.aa_sizes)]
+
+
 def test_probe_library_is_separate_from_the_product(api):
     """bench.py's MFMA-rate probe lives in its own shared object; the attention library does not export it."""
     from paper_2505_23520_amd import probe
