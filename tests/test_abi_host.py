@@ -38,18 +38,22 @@ def test_header_symbols_are_exported(api):
 
 
 def test_header_is_plain_c(tmp_path):
-    """The boundary is a C ABI: the header compiles as C99 on its own, and the struct the binding
-    declares has the size the C compiler gives it."""
+    """The boundary is a C ABI: the header compiles as C99 on its own, and the structs the binding
+    declares have the sizes and field offsets the C compiler gives them."""
     import subprocess
     src = tmp_path / "hdr.c"
-    src.write_text('#include "anchor_attention.h"\n#include <stdio.h>\n'
-                   'int main(void) { printf("%zu %zu\\n", sizeof(aa_params), sizeof(aa_sizes)); return 0; }\n')
+    from paper_2505_23520_amd import api as _api
+    structs = (("aa_params", _api.aa_params), ("aa_sizes", _api.aa_sizes))
+    prints = "".join('printf("%%zu\\n", sizeof(%s));\n' % name for name, _ in structs)
+    prints += "".join('printf("%%zu\\n", offsetof(%s, %s));\n' % (name, f[0]) for name, t in structs for f in t._fields_)
+    src.write_text('#include "anchor_attention.h"\n#include <stddef.h>\n#include <stdio.h>\n'
+                   'int main(void) {\n' + prints + 'return 0; }\n')
     exe = tmp_path / "hdr"
     subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror",
                            "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
-    sizes = subprocess.check_output([str(exe)], text=True).split()
-    from paper_2505_23520_amd import api as _api
-    assert [int(x) for x in sizes] == [ctypes.sizeof(_api.aa_params), ctypes.sizeof(_api.aa_sizes)]
+    got = [int(x) for x in subprocess.check_output([str(exe)], text=True).split()]
+    want = [ctypes.sizeof(t) for _, t in structs] + [getattr(t, f[0]).offset for _, t in structs for f in t._fields_]
+    assert got == want
 
 
 def test_probe_library_is_separate_from_the_product(api):
